@@ -1,0 +1,585 @@
+/*
+ * CPU oracle for batched function-secret-sharing KeyGen / Eval (equality and comparison).
+ *
+ * THIS FILE IS TEST INFRASTRUCTURE.  It is the slow, plain statement of what the HIP
+ * library must compute, written from the paper and sharing no code, table or header with
+ * the HIP path.  Only the tests, the smoke check and the benchmark's CPU-baseline leg may
+ * load it; the product never does.
+ *
+ * What it follows (AriaNN, arXiv 2006.04593):
+ *   - equality KeyGen / Eval: Algorithms 1 and 2 (section 3.1);
+ *   - comparison KeyGen / Eval for x <= alpha: Algorithms 3 and 4 (section 3.2);
+ *   - the shortened correction words of the "Implementation" paragraphs of sections 3.1
+ *     and 3.2.4: the lambda-bit string published for the branch that LEAVES the special
+ *     path is reused for the branch that stays on it, so a correction word carries one
+ *     seed-sized string and two control bits (plus one n-bit string and two bits for the
+ *     comparison lane) instead of two of each;
+ *   - the PRG of section 3.1 / appendix C.1: G(s) = E_k1(s)^s || E_k2(s)^s || E_k3(s)^s
+ *     with AES-128 under fixed keys (Matyas-Meyer-Oseas).
+ *
+ * AES-128 itself follows FIPS-197 byte by byte (S-box built from the field inverse and the
+ * affine map, no lookup tables typed in, no intrinsics).
+ *
+ * Pins (tests/test_oracle_*.py): FIPS-197 known answers and the OpenSSL command-line tool
+ * for AES; the correctness definition Eval_0 + Eval_1 = f(x) mod 2^n for EVERY x at n = 8
+ * and n = 12 and for sampled / edge x at n = 32; the per-level facts of the correctness
+ * proof of section 3.2.2 via the trace entry points; "step n+1 is the equality case";
+ * the closed-form key size of section 3.2.4.
+ * The value of an individual share depends on conventions the paper leaves open (fixed AES
+ * keys, byte order, where sigma/tau sit in the PRG output); those are this build's readings,
+ * stated below, and the share bits are therefore "parity unpinned" against any outside
+ * implementation: nothing the paper prints fixes them.
+ *
+ * Readings fixed here (each is a choice among equally correct ones):
+ *   block      16 bytes b[0..15] in FIPS-197 order; control bit t = b[0] & 1; the seed is
+ *              the block with that bit cleared (127 seed bits + t in one AES block, which is
+ *              how appendix C.1 gets away with one block per branch).
+ *   AES keys   k_m[i] = i for i < 15, k_m[15] = 0x0f + (m-1), m = 1,2,3.
+ *   G_1, G_2   left / right child block: t^b = bit 0 of byte 0, s^b = block with it cleared.
+ *   G_3        W: sigma^L = LE32(W[0..3]), sigma^R = LE32(W[4..7]) (masked to n bits),
+ *              tau^L = W[8] & 1, tau^R = (W[8] >> 1) & 1.
+ *   conv(s)    the map {0,1}^lambda -> Z_{2^n} in "1 - s_0 + s_1": LE32(s[12..15]) mod 2^n.
+ *   x[i]       i = 1..n counts from the most significant of the n bits; <= is unsigned.
+ *
+ * Key buffer layout (one party; little-endian u32; Bp = batch rounded up to 64 elements;
+ * planes follow each other without gaps):
+ *   comparison: alpha_share[Bp] u32 | seed[Bp][16] | ctrl[Bp][4] u32 (t_CW^L, t_CW^R,
+ *               tau_CW^L, tau_CW^R; bit i-1 belongs to level i) | s_CW[n][Bp][16] |
+ *               sigma_CW[n][Bp] u32 | CW_leaf[n][Bp] u32 | CW_leaf^(n+1)[Bp] u32
+ *   equality:   alpha_share[Bp] u32 | seed[Bp][16] | ctrl[Bp][2] u32 (t_CW^L, t_CW^R) |
+ *               s_CW[n][Bp][16] | CW^(n+1)[Bp] u32
+ * Padding elements (index >= batch) are written as zero by KeyGen.
+ */
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_OK 0
+#define ORACLE_EINVAL (-1)
+
+/* ------------------------------------------------------------------------------------ */
+/* AES-128 encryption, FIPS-197                                                          */
+/* ------------------------------------------------------------------------------------ */
+
+static uint8_t g_sbox[256];
+static uint8_t g_mul2[256], g_mul3[256];   /* x -> 2.x and 3.x in GF(2^8), filled from gf_mul */
+static int g_sbox_ready = 0;
+
+/* multiplication in GF(2^8) modulo x^8 + x^4 + x^3 + x + 1 (FIPS-197 section 4.2) */
+static uint8_t gf_mul(uint8_t a, uint8_t b)
+{
+    uint8_t p = 0;
+    for (int k = 0; k < 8; k++) {
+        if (b & 1) p ^= a;
+        uint8_t carry = a & 0x80;
+        a = (uint8_t)(a << 1);
+        if (carry) a ^= 0x1b;
+        b >>= 1;
+    }
+    return p;
+}
+
+/* S-box = affine map of the multiplicative inverse (FIPS-197 section 5.1.1) */
+static void build_sbox(void)
+{
+    for (int x = 0; x < 256; x++) {
+        uint8_t inv = 0;
+        if (x != 0) {
+            for (int y = 1; y < 256; y++) {
+                if (gf_mul((uint8_t)x, (uint8_t)y) == 1) { inv = (uint8_t)y; break; }
+            }
+        }
+        uint8_t out = 0;
+        for (int i = 0; i < 8; i++) {
+            int bit = ((inv >> i) ^ (inv >> ((i + 4) % 8)) ^ (inv >> ((i + 5) % 8)) ^
+                       (inv >> ((i + 6) % 8)) ^ (inv >> ((i + 7) % 8)) ^ (0x63 >> i)) & 1;
+            out |= (uint8_t)(bit << i);
+        }
+        g_sbox[x] = out;
+        g_mul2[x] = gf_mul((uint8_t)x, 2);
+        g_mul3[x] = gf_mul((uint8_t)x, 3);
+    }
+}
+
+static void aes128_expand_key(const uint8_t key[16], uint8_t rk[176]);
+void oracle_prg_key(int m, uint8_t key[16]);
+
+/* expanded round keys of the three fixed PRG keys, filled once by oracle_init() */
+static uint8_t g_prg_rk[3][176];
+
+void oracle_init(void)
+{
+    if (g_sbox_ready) return;
+    build_sbox();
+    for (int m = 1; m <= 3; m++) {
+        uint8_t key[16];
+        oracle_prg_key(m, key);
+        aes128_expand_key(key, g_prg_rk[m - 1]);
+    }
+    g_sbox_ready = 1;
+}
+
+/* key expansion, FIPS-197 section 5.2: 44 words, word w = bytes rk[4w..4w+3] */
+static void aes128_expand_key(const uint8_t key[16], uint8_t rk[176])
+{
+    memcpy(rk, key, 16);
+    uint8_t rcon = 0x01;
+    for (int w = 4; w < 44; w++) {
+        uint8_t tmp[4];
+        memcpy(tmp, rk + 4 * (w - 1), 4);
+        if (w % 4 == 0) {
+            uint8_t first = tmp[0];                       /* RotWord */
+            tmp[0] = tmp[1]; tmp[1] = tmp[2]; tmp[2] = tmp[3]; tmp[3] = first;
+            for (int k = 0; k < 4; k++) tmp[k] = g_sbox[tmp[k]];   /* SubWord */
+            tmp[0] ^= rcon;
+            rcon = gf_mul(rcon, 2);
+        }
+        for (int k = 0; k < 4; k++) rk[4 * w + k] = rk[4 * (w - 4) + k] ^ tmp[k];
+    }
+}
+
+/* state byte (row r, column c) lives at st[4c + r], which is also the input byte order */
+static void aes128_encrypt_rk(const uint8_t rk[176], const uint8_t in[16], uint8_t out[16])
+{
+    uint8_t st[16], tmp[16];
+    for (int i = 0; i < 16; i++) st[i] = in[i] ^ rk[i];
+    for (int round = 1; round <= 10; round++) {
+        for (int i = 0; i < 16; i++) st[i] = g_sbox[st[i]];               /* SubBytes */
+        for (int c = 0; c < 4; c++)                                        /* ShiftRows */
+            for (int r = 0; r < 4; r++) tmp[4 * c + r] = st[4 * ((c + r) % 4) + r];
+        if (round < 10) {                                                  /* MixColumns */
+            for (int c = 0; c < 4; c++) {
+                const uint8_t *a = tmp + 4 * c;
+                st[4 * c + 0] = g_mul2[a[0]] ^ g_mul3[a[1]] ^ a[2] ^ a[3];
+                st[4 * c + 1] = a[0] ^ g_mul2[a[1]] ^ g_mul3[a[2]] ^ a[3];
+                st[4 * c + 2] = a[0] ^ a[1] ^ g_mul2[a[2]] ^ g_mul3[a[3]];
+                st[4 * c + 3] = g_mul3[a[0]] ^ a[1] ^ a[2] ^ g_mul2[a[3]];
+            }
+        } else {
+            memcpy(st, tmp, 16);
+        }
+        for (int i = 0; i < 16; i++) st[i] ^= rk[16 * round + i];          /* AddRoundKey */
+    }
+    memcpy(out, st, 16);
+}
+
+void oracle_aes128_encrypt(const uint8_t key[16], const uint8_t in[16], uint8_t out[16])
+{
+    uint8_t rk[176];
+    oracle_init();
+    aes128_expand_key(key, rk);
+    aes128_encrypt_rk(rk, in, out);
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* PRG: G_m(s) = E_{k_m}(s) xor s, fixed keys (section 3.1 "Implementation", app. C.1)   */
+/* ------------------------------------------------------------------------------------ */
+
+void oracle_prg_key(int m, uint8_t key[16])
+{
+    for (int i = 0; i < 16; i++) key[i] = (uint8_t)i;
+    key[15] = (uint8_t)(0x0f + (m - 1));
+}
+
+/* m = 1, 2, 3.  `block` may carry a control bit in bit 0 of byte 0; it is cleared first. */
+void oracle_prg(int m, const uint8_t block[16], uint8_t out[16])
+{
+    uint8_t seed[16], enc[16];
+    oracle_init();
+    memcpy(seed, block, 16);
+    seed[0] &= 0xfe;
+    aes128_encrypt_rk(g_prg_rk[m - 1], seed, enc);
+    for (int i = 0; i < 16; i++) out[i] = enc[i] ^ seed[i];
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* helpers in the paper's notation                                                       */
+/* ------------------------------------------------------------------------------------ */
+
+enum { L = 0, R = 1 };
+
+static uint32_t ring_mask(int n) { return n == 32 ? 0xffffffffu : ((1u << n) - 1u); }
+
+static uint32_t le32(const uint8_t *p)
+{
+    return (uint32_t)p[0] | ((uint32_t)p[1] << 8) | ((uint32_t)p[2] << 16) | ((uint32_t)p[3] << 24);
+}
+
+static void put_le32(uint8_t *p, uint32_t v)
+{
+    p[0] = (uint8_t)v; p[1] = (uint8_t)(v >> 8); p[2] = (uint8_t)(v >> 16); p[3] = (uint8_t)(v >> 24);
+}
+
+/* x[i], i = 1..n, most significant of the n bits first */
+static int bit_of(uint32_t x, int n, int i) { return (int)((x >> (n - i)) & 1u); }
+
+/* the implicit map from a lambda-bit string to Z_{2^n} used by the final correction word */
+static uint32_t conv(const uint8_t s[16], int n) { return le32(s + 12) & ring_mask(n); }
+
+/* everything G(s) yields for one seed: (s^L||t^L, s^R||t^R), (sigma^L||tau^L, sigma^R||tau^R) */
+typedef struct {
+    uint8_t s[2][16];
+    int t[2];
+    uint32_t sigma[2];
+    int tau[2];
+} expansion_t;
+
+static void expand(const uint8_t seed[16], int n, int with_sigma, expansion_t *e)
+{
+    for (int b = 0; b < 2; b++) {
+        uint8_t blk[16];
+        oracle_prg(1 + b, seed, blk);
+        e->t[b] = blk[0] & 1;
+        blk[0] &= 0xfe;
+        memcpy(e->s[b], blk, 16);
+    }
+    e->sigma[L] = e->sigma[R] = 0;
+    e->tau[L] = e->tau[R] = 0;
+    if (with_sigma) {
+        uint8_t w[16];
+        oracle_prg(3, seed, w);
+        e->sigma[L] = le32(w + 0) & ring_mask(n);
+        e->sigma[R] = le32(w + 4) & ring_mask(n);
+        e->tau[L] = w[8] & 1;
+        e->tau[R] = (w[8] >> 1) & 1;
+    }
+}
+
+static void xor16_if(uint8_t dst[16], const uint8_t cw[16], int apply)
+{
+    if (apply) for (int k = 0; k < 16; k++) dst[k] ^= cw[k];
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* key buffer layout                                                                     */
+/* ------------------------------------------------------------------------------------ */
+
+static size_t padded(size_t batch) { return (batch + 63) / 64 * 64; }
+
+typedef struct {
+    size_t bp;
+    int n;
+    uint8_t *alpha_share, *seed, *ctrl, *s_cw, *sigma_cw, *leaf, *last;
+    int ctrl_words;
+} key_view_t;
+
+static size_t view_cmp(key_view_t *v, void *base, int n, size_t batch)
+{
+    size_t bp = padded(batch);
+    uint8_t *p = (uint8_t *)base;
+    v->bp = bp; v->n = n; v->ctrl_words = 4;
+    v->alpha_share = p;                 p += 4 * bp;
+    v->seed = p;                        p += 16 * bp;
+    v->ctrl = p;                        p += 16 * bp;
+    v->s_cw = p;                        p += (size_t)n * 16 * bp;
+    v->sigma_cw = p;                    p += (size_t)n * 4 * bp;
+    v->leaf = p;                        p += (size_t)n * 4 * bp;
+    v->last = p;                        p += 4 * bp;
+    return (size_t)(p - (uint8_t *)base);
+}
+
+static size_t view_eq(key_view_t *v, void *base, int n, size_t batch)
+{
+    size_t bp = padded(batch);
+    uint8_t *p = (uint8_t *)base;
+    v->bp = bp; v->n = n; v->ctrl_words = 2;
+    v->alpha_share = p;                 p += 4 * bp;
+    v->seed = p;                        p += 16 * bp;
+    v->ctrl = p;                        p += 8 * bp;
+    v->s_cw = p;                        p += (size_t)n * 16 * bp;
+    v->sigma_cw = NULL; v->leaf = NULL;
+    v->last = p;                        p += 4 * bp;
+    return (size_t)(p - (uint8_t *)base);
+}
+
+static int bad_n(int n) { return n < 1 || n > 32; }
+
+size_t oracle_cmp_key_bytes(int n, size_t batch)
+{
+    key_view_t v;
+    if (bad_n(n)) return 0;
+    return view_cmp(&v, NULL, n, batch);
+}
+
+size_t oracle_eq_key_bytes(int n, size_t batch)
+{
+    key_view_t v;
+    if (bad_n(n)) return 0;
+    return view_eq(&v, NULL, n, batch);
+}
+
+/* bits of ONE element's key as the paper counts them (section 3.2.4; section 3.1) */
+size_t oracle_cmp_key_bits_logical(int n) { return (size_t)n * (128 + 2 * (size_t)n + 4) + 128 + 2 * (size_t)n; }
+size_t oracle_eq_key_bits_logical(int n) { return (size_t)n + 128 + (size_t)n * (128 + 2) + (size_t)n; }
+
+static uint8_t *s_cw_at(const key_view_t *v, int level, size_t e) { return v->s_cw + ((size_t)(level - 1) * v->bp + e) * 16; }
+static uint8_t *sigma_cw_at(const key_view_t *v, int level, size_t e) { return v->sigma_cw + ((size_t)(level - 1) * v->bp + e) * 4; }
+static uint8_t *leaf_at(const key_view_t *v, int level, size_t e) { return v->leaf + ((size_t)(level - 1) * v->bp + e) * 4; }
+static uint32_t ctrl_word(const key_view_t *v, size_t e, int which) { return le32(v->ctrl + (e * v->ctrl_words + which) * 4); }
+static int ctrl_bit(const key_view_t *v, size_t e, int which, int level) { return (int)((ctrl_word(v, e, which) >> (level - 1)) & 1u); }
+
+/* ------------------------------------------------------------------------------------ */
+/* KeyGen (Algorithm 1 = the (s,t) lane only; Algorithm 3 = with the (sigma,tau) lane)   */
+/* ------------------------------------------------------------------------------------ */
+
+static void keygen_one(int cmp, int n, uint32_t alpha, uint32_t r, const uint8_t *seed0, const uint8_t *seed1,
+                       const key_view_t *k0, const key_view_t *k1, size_t e)
+{
+    const uint32_t mask = ring_mask(n);
+    const key_view_t *kk[2] = { k0, k1 };
+    uint8_t s[2][16];
+    int t[2] = { 0, 1 };                           /* t_j^(1) = j */
+    uint32_t ctrl[4] = { 0, 0, 0, 0 };
+
+    alpha &= mask; r &= mask;
+    memcpy(s[0], seed0, 16); s[0][0] &= 0xfe;
+    memcpy(s[1], seed1, 16); s[1][0] &= 0xfe;
+
+    /* k_j starts with [[alpha]]_j and s_j^(1) */
+    put_le32(k0->alpha_share + 4 * e, r);
+    put_le32(k1->alpha_share + 4 * e, (alpha - r) & mask);
+    memcpy(k0->seed + 16 * e, s[0], 16);
+    memcpy(k1->seed + 16 * e, s[1], 16);
+
+    for (int i = 1; i <= n; i++) {
+        const int a = bit_of(alpha, n, i);
+        const int keep = a, lose = 1 - a;          /* branch index: L = 0, R = 1 */
+        expansion_t g[2];
+        expand(s[0], n, cmp, &g[0]);
+        expand(s[1], n, cmp, &g[1]);
+
+        /* CW^(i), (s,t) part: the Lose-side string is published once and serves both
+         * branches; the control bits make t_0 xor t_1 equal 1 on Keep and 0 on Lose */
+        uint8_t s_cw[16];
+        for (int k = 0; k < 16; k++) s_cw[k] = g[0].s[lose][k] ^ g[1].s[lose][k];
+        int t_cw[2];
+        t_cw[L] = g[0].t[L] ^ g[1].t[L] ^ a ^ 1;   /* L is Keep iff a = 0 */
+        t_cw[R] = g[0].t[R] ^ g[1].t[R] ^ a;       /* R is Keep iff a = 1 */
+
+        /* CW^(i), (sigma,tau) part: the roles swap -- the lane must carry a share of a
+         * leaf label exactly on the branch that leaves the path, so the published n-bit
+         * string is the Keep-side one (cancels there) and tau_0 xor tau_1 = 1 on Lose */
+        uint32_t sigma_cw = 0;
+        int tau_cw[2] = { 0, 0 };
+        uint32_t cw_leaf = 0;
+        if (cmp) {
+            sigma_cw = g[0].sigma[keep] ^ g[1].sigma[keep];
+            tau_cw[L] = g[0].tau[L] ^ g[1].tau[L] ^ a;        /* L is Lose iff a = 1 */
+            tau_cw[R] = g[0].tau[R] ^ g[1].tau[R] ^ a ^ 1;    /* R is Lose iff a = 0 */
+
+            /* sigma_j^(i+1) || tau_j^(i+1) = state'_{j, 1 - alpha[i]} */
+            uint32_t sigma_next[2];
+            int tau_next[2];
+            for (int j = 0; j < 2; j++) {
+                sigma_next[j] = g[j].sigma[lose] ^ (t[j] ? sigma_cw : 0u);
+                tau_next[j] = g[j].tau[lose] ^ (t[j] & tau_cw[lose]);
+            }
+            /* CW_leaf^(i) = (-1)^{tau_1} (alpha[i] - sigma_0 + sigma_1) mod 2^n */
+            cw_leaf = ((uint32_t)a - sigma_next[0] + sigma_next[1]) & mask;
+            if (tau_next[1]) cw_leaf = (0u - cw_leaf) & mask;
+        }
+
+        /* s_j^(i+1) || t_j^(i+1) = state_{j, alpha[i]}, both from the OLD t_j^(i) */
+        for (int j = 0; j < 2; j++) {
+            uint8_t next[16];
+            memcpy(next, g[j].s[keep], 16);
+            xor16_if(next, s_cw, t[j]);
+            int t_next = g[j].t[keep] ^ (t[j] & t_cw[keep]);
+            memcpy(s[j], next, 16);
+            t[j] = t_next;
+        }
+
+        /* the correction words are common to both keys */
+        ctrl[0] |= (uint32_t)t_cw[L] << (i - 1);
+        ctrl[1] |= (uint32_t)t_cw[R] << (i - 1);
+        ctrl[2] |= (uint32_t)tau_cw[L] << (i - 1);
+        ctrl[3] |= (uint32_t)tau_cw[R] << (i - 1);
+        for (int j = 0; j < 2; j++) {
+            memcpy(s_cw_at(kk[j], i, e), s_cw, 16);
+            if (cmp) {
+                put_le32(sigma_cw_at(kk[j], i, e), sigma_cw);
+                put_le32(leaf_at(kk[j], i, e), cw_leaf);
+            }
+        }
+    }
+
+    /* CW^(n+1) = (-1)^{t_1^(n+1)} (1 - s_0^(n+1) + s_1^(n+1)) mod 2^n */
+    uint32_t last = (1u - conv(s[0], n) + conv(s[1], n)) & mask;
+    if (t[1]) last = (0u - last) & mask;
+    for (int j = 0; j < 2; j++) {
+        put_le32(kk[j]->last + 4 * e, last);
+        for (int w = 0; w < kk[j]->ctrl_words; w++)
+            put_le32(kk[j]->ctrl + (e * kk[j]->ctrl_words + w) * 4, ctrl[w]);
+    }
+}
+
+static int keygen_batch(int cmp, int n, size_t batch, const uint32_t *alpha, const uint32_t *alpha_r,
+                        const uint8_t *seed0, const uint8_t *seed1, void *key0, void *key1)
+{
+    if (bad_n(n)) return ORACLE_EINVAL;
+    if (batch == 0) return ORACLE_OK;
+    if (!alpha || !alpha_r || !seed0 || !seed1 || !key0 || !key1) return ORACLE_EINVAL;
+    oracle_init();
+    key_view_t k0, k1;
+    size_t bytes = cmp ? view_cmp(&k0, key0, n, batch) : view_eq(&k0, key0, n, batch);
+    if (cmp) view_cmp(&k1, key1, n, batch); else view_eq(&k1, key1, n, batch);
+    memset(key0, 0, bytes);
+    memset(key1, 0, bytes);
+    long long b = (long long)batch;
+#pragma omp parallel for schedule(static)
+    for (long long e = 0; e < b; e++)
+        keygen_one(cmp, n, alpha[e], alpha_r[e], seed0 + 16 * e, seed1 + 16 * e, &k0, &k1, (size_t)e);
+    return ORACLE_OK;
+}
+
+int oracle_cmp_gen(int n, size_t batch, const uint32_t *alpha, const uint32_t *alpha_r,
+                   const uint8_t *seed0, const uint8_t *seed1, void *key0, void *key1)
+{
+    return keygen_batch(1, n, batch, alpha, alpha_r, seed0, seed1, key0, key1);
+}
+
+int oracle_eq_gen(int n, size_t batch, const uint32_t *alpha, const uint32_t *alpha_r,
+                  const uint8_t *seed0, const uint8_t *seed1, void *key0, void *key1)
+{
+    return keygen_batch(0, n, batch, alpha, alpha_r, seed0, seed1, key0, key1);
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* Eval (Algorithm 2; Algorithm 4)                                                       */
+/* ------------------------------------------------------------------------------------ */
+
+/* Optional per-level record of one evaluation, for the tests of the correctness proof. */
+typedef struct {
+    uint8_t (*s)[16];   /* [n+1]: s^(2) .. s^(n+1) at index 1..n, s^(1) at index 0 */
+    int32_t *t;         /* [n+1] */
+    uint32_t *sigma;    /* [n+1], index i = sigma^(i+1), index 0 unused */
+    int32_t *tau;       /* [n+1] */
+    uint32_t *out;      /* [n+2], index i = out_i before the (-1)^j factor, i = 1..n+1 */
+} trace_t;
+
+static uint32_t eval_one(int cmp, int party, int n, const key_view_t *k, size_t e, uint32_t x, trace_t *tr)
+{
+    const uint32_t mask = ring_mask(n);
+    uint8_t s[16];
+    int t = party;                                   /* t^(1) = j */
+    uint32_t acc = 0;
+    x &= mask;
+    memcpy(s, k->seed + 16 * e, 16);
+    s[0] &= 0xfe;
+    if (tr) { memcpy(tr->s[0], s, 16); tr->t[0] = t; }
+
+    for (int i = 1; i <= n; i++) {
+        const int b = bit_of(x, n, i);
+        expansion_t g;
+        expand(s, n, cmp, &g);
+        /* state = G(s^(i)) xor (t^(i) . CW^(i)); only the x[i] halves are needed */
+        if (cmp) {
+            uint32_t sigma = g.sigma[b] ^ (t ? le32(sigma_cw_at(k, i, e)) : 0u);
+            int tau = g.tau[b] ^ (t & ctrl_bit(k, e, 2 + b, i));
+            /* out_i = tau^(i+1) . CW_leaf^(i) + sigma^(i+1)   (sign applied at the end) */
+            uint32_t out_i = ((tau ? le32(leaf_at(k, i, e)) : 0u) + sigma) & mask;
+            acc = (acc + out_i) & mask;
+            if (tr) { tr->sigma[i] = sigma; tr->tau[i] = tau; tr->out[i] = out_i; }
+        }
+        uint8_t next[16];
+        memcpy(next, g.s[b], 16);
+        xor16_if(next, s_cw_at(k, i, e), t);
+        int t_next = g.t[b] ^ (t & ctrl_bit(k, e, b, i));
+        memcpy(s, next, 16);
+        t = t_next;
+        if (tr) { memcpy(tr->s[i], s, 16); tr->t[i] = t; }
+    }
+    /* out_{n+1} = t^(n+1) . CW^(n+1) + s^(n+1) */
+    uint32_t out_last = ((t ? le32(k->last + 4 * e) : 0u) + conv(s, n)) & mask;
+    acc = (acc + out_last) & mask;
+    if (tr) tr->out[n + 1] = out_last;
+    /* [[T]]_j = (-1)^j . sum_i out_i mod 2^n */
+    if (party == 1) acc = (0u - acc) & mask;
+    return acc;
+}
+
+static int eval_batch(int cmp, int party, int n, size_t batch, const void *key, const uint32_t *x, uint32_t *out)
+{
+    if (bad_n(n) || (party != 0 && party != 1)) return ORACLE_EINVAL;
+    if (batch == 0) return ORACLE_OK;
+    if (!key || !x || !out) return ORACLE_EINVAL;
+    oracle_init();
+    key_view_t k;
+    if (cmp) view_cmp(&k, (void *)key, n, batch); else view_eq(&k, (void *)key, n, batch);
+    long long b = (long long)batch;
+#pragma omp parallel for schedule(static)
+    for (long long e = 0; e < b; e++)
+        out[e] = eval_one(cmp, party, n, &k, (size_t)e, x[e], NULL);
+    return ORACLE_OK;
+}
+
+int oracle_cmp_eval(int party, int n, size_t batch, const void *key, const uint32_t *x, uint32_t *out)
+{
+    return eval_batch(1, party, n, batch, key, x, out);
+}
+
+int oracle_eq_eval(int party, int n, size_t batch, const void *key, const uint32_t *x, uint32_t *out)
+{
+    return eval_batch(0, party, n, batch, key, x, out);
+}
+
+/* Evaluate element `e` of a key buffer on ALL 2^n inputs x = 0 .. 2^n - 1 (n <= 16). */
+static int eval_all_x(int cmp, int party, int n, size_t batch, const void *key, size_t e, uint32_t *out)
+{
+    if (bad_n(n) || n > 16 || (party != 0 && party != 1) || e >= batch || !key || !out) return ORACLE_EINVAL;
+    oracle_init();
+    key_view_t k;
+    if (cmp) view_cmp(&k, (void *)key, n, batch); else view_eq(&k, (void *)key, n, batch);
+    long long count = 1ll << n;
+#pragma omp parallel for schedule(static)
+    for (long long x = 0; x < count; x++)
+        out[x] = eval_one(cmp, party, n, &k, e, (uint32_t)x, NULL);
+    return ORACLE_OK;
+}
+
+int oracle_cmp_eval_all_x(int party, int n, size_t batch, const void *key, size_t e, uint32_t *out)
+{
+    return eval_all_x(1, party, n, batch, key, e, out);
+}
+
+int oracle_eq_eval_all_x(int party, int n, size_t batch, const void *key, size_t e, uint32_t *out)
+{
+    return eval_all_x(0, party, n, batch, key, e, out);
+}
+
+/* One evaluation with every intermediate exposed.  s: [n+1][16], t/sigma/tau: [n+1],
+ * outs: [n+2]; index i holds the value AFTER level i (index 0: the initial state). */
+int oracle_eval_trace(int cmp, int party, int n, size_t batch, const void *key, size_t e, uint32_t x,
+                      uint8_t *s, int32_t *t, uint32_t *sigma, int32_t *tau, uint32_t *outs, uint32_t *share)
+{
+    if (bad_n(n) || (party != 0 && party != 1) || e >= batch || !key) return ORACLE_EINVAL;
+    oracle_init();
+    key_view_t k;
+    if (cmp) view_cmp(&k, (void *)key, n, batch); else view_eq(&k, (void *)key, n, batch);
+    trace_t tr;
+    tr.s = (uint8_t (*)[16])s; tr.t = t; tr.sigma = sigma; tr.tau = tau; tr.out = outs;
+    memset(sigma, 0, sizeof(uint32_t) * (size_t)(n + 1));
+    memset(tau, 0, sizeof(int32_t) * (size_t)(n + 1));
+    memset(outs, 0, sizeof(uint32_t) * (size_t)(n + 2));
+    *share = eval_one(cmp, party, n, &k, e, x, &tr);
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* threading of the batch loops (used only by the benchmark's CPU-baseline leg)          */
+/* ------------------------------------------------------------------------------------ */
+
+int oracle_set_threads(int threads)
+{
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+    return omp_get_max_threads();
+#else
+    (void)threads;
+    return 1;
+#endif
+}

@@ -1,0 +1,97 @@
+"""Do the pins bite?  Each case plants ONE plausible mistake (a dropped term, a wrong sign
+or index, swapped operands) in a temporary copy of the oracle's C source, builds it on the
+CPU, and checks that the pins of test_oracle_aes / test_oracle_fss reject it.  The mistakes
+live only in the temporary copy; nothing here touches the GPU."""
+import os
+import subprocess
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2006_04593_amd import workloads as W
+
+SRC = os.path.join(os.path.dirname(oracle.__file__), "fss_oracle.c")
+
+# (name, text in the oracle, replacement, which pin must fail)
+MUTANTS = [
+    ("leaf_sign_dropped", "if (tau_next[1]) cw_leaf = (0u - cw_leaf) & mask;", "", "cmp"),
+    ("leaf_operands_swapped", "cw_leaf = ((uint32_t)a - sigma_next[0] + sigma_next[1]) & mask;",
+     "cw_leaf = ((uint32_t)a + sigma_next[0] - sigma_next[1]) & mask;", "cmp"),
+    ("leaf_alpha_bit_dropped", "cw_leaf = ((uint32_t)a - sigma_next[0] + sigma_next[1]) & mask;",
+     "cw_leaf = (0u - sigma_next[0] + sigma_next[1]) & mask;", "cmp"),
+    ("t_cw_sides_swapped", "t_cw[L] = g[0].t[L] ^ g[1].t[L] ^ a ^ 1;", "t_cw[L] = g[0].t[L] ^ g[1].t[L] ^ a;", "both"),
+    ("tau_cw_sides_swapped", "tau_cw[L] = g[0].tau[L] ^ g[1].tau[L] ^ a;", "tau_cw[L] = g[0].tau[L] ^ g[1].tau[L] ^ a ^ 1;", "cmp"),
+    ("sigma_cw_from_lose_side", "sigma_cw = g[0].sigma[keep] ^ g[1].sigma[keep];", "sigma_cw = g[0].sigma[lose] ^ g[1].sigma[lose];", "cmp"),
+    ("s_cw_from_keep_side", "s_cw[k] = g[0].s[lose][k] ^ g[1].s[lose][k];", "s_cw[k] = g[0].s[keep][k] ^ g[1].s[keep][k];", "both"),
+    ("gen_walks_lose_branch", "memcpy(next, g[j].s[keep], 16);", "memcpy(next, g[j].s[lose], 16);", "both"),
+    ("bits_lsb_first", "return (int)((x >> (n - i)) & 1u);", "return (int)((x >> (i - 1)) & 1u);", "cmp"),
+    ("final_term_dropped", "acc = (acc + out_last) & mask;", "", "both"),
+    ("final_cw_sign_dropped", "if (t[1]) last = (0u - last) & mask;", "", "both"),
+    ("final_cw_constant_dropped", "uint32_t last = (1u - conv(s[0], n) + conv(s[1], n)) & mask;",
+     "uint32_t last = (0u - conv(s[0], n) + conv(s[1], n)) & mask;", "both"),
+    ("party_sign_dropped", "if (party == 1) acc = (0u - acc) & mask;", "", "both"),
+    ("eval_starts_with_t_zero", "int t = party;                                   /* t^(1) = j */", "int t = 0;", "both"),
+    ("eval_tau_uses_other_side", "int tau = g.tau[b] ^ (t & ctrl_bit(k, e, 2 + b, i));", "int tau = g.tau[b] ^ (t & ctrl_bit(k, e, 3 - b, i));", "cmp"),
+    ("eval_t_uses_other_side", "int t_next = g.t[b] ^ (t & ctrl_bit(k, e, b, i));", "int t_next = g.t[b] ^ (t & ctrl_bit(k, e, 1 - b, i));", "both"),
+    ("leaf_added_without_tau_gate", "uint32_t out_i = ((tau ? le32(leaf_at(k, i, e)) : 0u) + sigma) & mask;",
+     "uint32_t out_i = (le32(leaf_at(k, i, e)) + sigma) & mask;", "cmp"),
+    ("shiftrows_wrong_direction", "tmp[4 * c + r] = st[4 * ((c + r) % 4) + r];", "tmp[4 * c + r] = st[4 * ((c + 4 - r) % 4) + r];", "aes"),
+    ("mixcolumns_coefficients_swapped", "st[4 * c + 0] = g_mul2[a[0]] ^ g_mul3[a[1]] ^ a[2] ^ a[3];",
+     "st[4 * c + 0] = g_mul3[a[0]] ^ g_mul2[a[1]] ^ a[2] ^ a[3];", "aes"),
+    ("affine_constant_wrong", "(0x63 >> i)) & 1;", "(0x36 >> i)) & 1;", "aes"),
+    ("mmo_feedforward_dropped", "out[i] = enc[i] ^ seed[i];", "out[i] = enc[i];", "prg"),
+]
+
+
+def build_mutant(tmp_path, name, old, new):
+    text = open(SRC).read()
+    assert text.count(old) == 1, f"{name}: pattern must occur exactly once in the oracle source"
+    src = tmp_path / f"{name}.c"
+    so = tmp_path / f"lib{name}.so"
+    src.write_text(text.replace(old, new))
+    subprocess.run(["gcc", "-O1", "-std=c11", "-fopenmp", "-fPIC", "-shared", str(src), "-o", str(so)], check=True)
+    return oracle.load(str(so))
+
+
+def reconstruction_holds(kind, n=8):
+    rng = np.random.default_rng(31337)
+    alphas = np.concatenate([W.edge_inputs(n), W.uniform_ring(rng, n, 10)])
+    g = W.gen_inputs(rng, n, len(alphas), alpha=alphas)
+    k0, k1 = oracle.gen(kind, n, g.alpha, g.r, g.seed0, g.seed1)
+    xs = np.arange(1 << n, dtype=np.uint32)
+    for e, a in enumerate(g.alpha):
+        rec = (oracle.eval_all_x(kind, 0, n, g.batch, k0, e) + oracle.eval_all_x(kind, 1, n, g.batch, k1, e)) & np.uint32(W.ring_mask(n))
+        want = ((xs <= a) if kind == "cmp" else (xs == a)).astype(np.uint32)
+        if not np.array_equal(rec, want):
+            return False
+    return True
+
+
+def aes_known_answer_holds():
+    return oracle.aes128_encrypt(bytes(range(16)), bytes.fromhex("00112233445566778899aabbccddeeff")).hex() == \
+        "69c4e0d86a7b0430d8cdb78070b4c55a"
+
+
+def prg_definition_holds():
+    s = bytes(range(2, 34, 2))
+    enc = oracle.aes128_encrypt(oracle.prg_key(2), s)
+    return oracle.prg(2, s) == bytes(a ^ b for a, b in zip(enc, s))
+
+
+def test_unmodified_oracle_passes_the_compact_pins():
+    assert reconstruction_holds("cmp") and reconstruction_holds("eq")
+    assert aes_known_answer_holds() and prg_definition_holds()
+
+
+@pytest.mark.parametrize("name,old,new,pin", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_planted_mistake_is_caught(tmp_path, monkeypatch, name, old, new, pin):
+    monkeypatch.setattr(oracle, "_lib", build_mutant(tmp_path, name, old, new))
+    if pin == "aes":
+        assert not aes_known_answer_holds()
+    elif pin == "prg":
+        assert aes_known_answer_holds() and not prg_definition_holds()
+    elif pin == "cmp":
+        assert not reconstruction_holds("cmp")
+    else:
+        assert not reconstruction_holds("cmp") and not reconstruction_holds("eq")
