@@ -1,0 +1,122 @@
+/*
+ * fss.h -- C ABI of libfss_mi355: batched function-secret-sharing key generation and
+ * evaluation on one AMD MI355X (gfx950), for the two primitives of AriaNN
+ * (arXiv 2006.04593): equality 1{x = alpha} (section 3.1, Algorithms 1 and 2) and
+ * comparison 1{x <= alpha} (section 3.2, Algorithms 3 and 4), over the ring Z_{2^n},
+ * 1 <= n <= 32, with a 128-bit state block (127 seed bits + 1 control bit, appendix C.1).
+ *
+ * The syntax follows Definition 2.1 of the paper: KeyGen(1^lambda, f) -> (k_0, k_1) and
+ * Eval(j, k_j, x) -> the j-th additive share of f(x).  One call handles a batch of
+ * independent elements (one key per element), which is the paper's data-parallel "tensor"
+ * use of the primitives (section 4.1).  KeyGen's random choices (alpha and the two root
+ * seeds, sampled in the initialisation lines of Algorithms 1 and 3) are ARGUMENTS here, so
+ * that key generation is a deterministic, auditable function of its inputs.
+ *
+ * General rules
+ *   - Every pointer whose name starts with d_ is DEVICE memory on the current HIP device,
+ *     owned by the caller before, during and after the call.  The library allocates no
+ *     device memory, keeps no pointer, and holds no mutable state between calls.
+ *   - Calls only ENQUEUE work on `stream` (a hipStream_t; NULL = the default stream) and
+ *     return without waiting; the caller synchronises.  Buffers must stay valid until the
+ *     enqueued work has finished.
+ *   - Return value: FSS_OK (0) or a negative FSS_E* code; nothing aborts or throws.
+ *     Arguments are checked on the host before any device work is enqueued, so a failed
+ *     call has no effect.  batch == 0 is a successful no-op (pointers may then be NULL).
+ *   - Values of alpha, r and x are reduced mod 2^n (high bits ignored).
+ *   - Alignment: key buffers 256 bytes; seed arrays 16 bytes; u32 arrays 4 bytes.
+ *
+ * Key buffer (ONE party's keys for the whole batch; structure of arrays so that the 64
+ * lanes of a wavefront read consecutive addresses at every level).  Bp = batch rounded up
+ * to a multiple of 64; all integers little-endian; planes follow each other without gaps:
+ *
+ *   comparison key                                    bytes
+ *     alpha_share [Bp]      u32   [[alpha]]_j          4 Bp      (not read by Eval)
+ *     seed        [Bp][16]  u8    s_j^(1)              16 Bp
+ *     ctrl        [Bp][4]   u32   t_CW^L, t_CW^R,      16 Bp     bit i-1 <-> level i
+ *                                 tau_CW^L, tau_CW^R
+ *     s_CW        [n][Bp][16] u8                       16 n Bp
+ *     sigma_CW    [n][Bp]   u32                        4 n Bp
+ *     CW_leaf     [n][Bp]   u32   levels 1..n          4 n Bp
+ *     CW_leaf_last[Bp]      u32   level n+1            4 Bp
+ *   = 808 bytes per element at n = 32, the paper's n(lambda+2n+4)+lambda+2n bits (3.2.4).
+ *
+ *   equality key
+ *     alpha_share [Bp] u32 | seed [Bp][16] | ctrl [Bp][2] u32 (t_CW^L, t_CW^R) |
+ *     s_CW [n][Bp][16] | CW_last [Bp] u32                = 544 bytes per element at n = 32.
+ *
+ *   The correction-word planes of k_0 and k_1 are identical; the keys differ in seed and
+ *   alpha_share.  Elements batch..Bp-1 of every plane are padding (KeyGen leaves them
+ *   untouched; Eval never reads them).
+ *
+ * Conventions the paper leaves open, fixed by this library:
+ *   - block = 16 bytes in FIPS-197 order; control bit t = bit 0 of byte 0; a seed is a block
+ *     with that bit cleared.
+ *   - PRG (section 3.1 "Implementation", appendix C.1): G_m(s) = AES128_{k_m}(s) xor s with
+ *     fixed keys k_m = 00 01 .. 0e (0f + m - 1), m = 1, 2, 3.  G_1 / G_2 give the left /
+ *     right child block (s^b || t^b).  G_3 gives W with sigma^L = LE32(W[0..3]),
+ *     sigma^R = LE32(W[4..7]) (mod 2^n), tau^L = W[8] & 1, tau^R = (W[8] >> 1) & 1.
+ *   - the map from a seed to Z_{2^n} in the last correction word is LE32(s[12..15]) mod 2^n.
+ *   - x[i], alpha[i] for i = 1..n count from the most significant of the n bits; <= is the
+ *     unsigned order (section 2, "natural embedding").
+ *   - correction words are in the shortened form of the "Implementation" paragraphs: the
+ *     seed-sized string of the branch leaving the special path is reused for the branch
+ *     staying on it (and, for the sigma lane, the other way round).
+ */
+#ifndef FSS_MI355_H
+#define FSS_MI355_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef void *fss_stream_t; /* hipStream_t */
+
+#define FSS_OK 0
+#define FSS_EINVAL (-1)   /* party not in {0,1}; n not in [1,32]; NULL or misaligned pointer with batch > 0 */
+#define FSS_ELAUNCH (-2)  /* the HIP runtime refused a launch or an attribute; see fss_last_hip_error() */
+#define FSS_EDEVICE (-3)  /* current device cannot run the kernels (needs 128 KiB of LDS per workgroup) */
+
+/* Size in bytes of ONE party's key buffer for `batch` elements, padding included
+ * (808 * Bp for comparison and 544 * Bp for equality at n = 32).  0 if n is out of range. */
+size_t fss_cmp_key_bytes(int n, size_t batch);
+size_t fss_eq_key_bytes(int n, size_t batch);
+
+/* Comparison KeyGen, Algorithm 3 of the paper: for every element e < batch builds the pair
+ * (k_0, k_1) of keys for f(x) = 1{x <= alpha[e]}.
+ *   d_alpha   [batch] u32   the secret offsets alpha
+ *   d_alpha_r [batch] u32   randomness r: [[alpha]]_0 = r, [[alpha]]_1 = alpha - r (mod 2^n)
+ *   d_seed0   [batch][16]   party 0's root seed blocks s_0^(1) (bit 0 of byte 0 is ignored)
+ *   d_seed1   [batch][16]   party 1's root seed blocks s_1^(1)
+ *   d_key0, d_key1          out: fss_cmp_key_bytes(n, batch) bytes each, must not overlap */
+int fss_cmp_gen(int n, size_t batch, const uint32_t *d_alpha, const uint32_t *d_alpha_r,
+                const uint8_t *d_seed0, const uint8_t *d_seed1, void *d_key0, void *d_key1,
+                fss_stream_t stream);
+
+/* Comparison Eval, Algorithm 4: d_out[e] = party `party`'s share of 1{d_x[e] <= alpha[e]},
+ * so that d_out(party 0) + d_out(party 1) = 1{x <= alpha} mod 2^n.
+ *   d_key  that party's key buffer as written by fss_cmp_gen (same n and batch)
+ *   d_x    [batch] u32 public inputs;   d_out [batch] u32 */
+int fss_cmp_eval(int party, int n, size_t batch, const void *d_key, const uint32_t *d_x,
+                 uint32_t *d_out, fss_stream_t stream);
+
+/* Equality KeyGen / Eval, Algorithms 1 and 2; same argument meaning, f(x) = 1{x = alpha},
+ * key buffers of fss_eq_key_bytes(n, batch) bytes. */
+int fss_eq_gen(int n, size_t batch, const uint32_t *d_alpha, const uint32_t *d_alpha_r,
+               const uint8_t *d_seed0, const uint8_t *d_seed1, void *d_key0, void *d_key1,
+               fss_stream_t stream);
+int fss_eq_eval(int party, int n, size_t batch, const void *d_key, const uint32_t *d_x,
+                uint32_t *d_out, fss_stream_t stream);
+
+/* Text for a return code (static storage, never NULL). */
+const char *fss_strerror(int code);
+
+/* The hipError_t value behind the most recent FSS_ELAUNCH / FSS_EDEVICE on this thread. */
+int fss_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FSS_MI355_H */

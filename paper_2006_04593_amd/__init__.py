@@ -1,0 +1,18 @@
+"""MI355X-native batched function-secret-sharing KeyGen / Eval (AriaNN, arXiv 2006.04593).
+
+The work happens in libfss_mi355.so (hand-written HIP for gfx950 behind the C ABI of
+include/fss.h); this package only marshals arguments.  There is no CPU fallback: if the
+library has not been built, importing `binding` functions raises.
+"""
+from .binding import (  # noqa: F401
+    FssError,
+    build,
+    cmp_eval,
+    cmp_gen,
+    cmp_key_bytes,
+    eq_eval,
+    eq_gen,
+    eq_key_bytes,
+    lib,
+    library_path,
+)

@@ -1,0 +1,121 @@
+"""Thin ctypes binding over the C ABI of include/fss.h -- same names, argument marshalling
+only.  Tensors are PyTorch CUDA(HIP) tensors used purely as device buffers; every step of
+key generation and evaluation runs inside the HIP kernels of libfss_mi355.so."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_CSRC = os.path.join(_HERE, "csrc")
+_SO = os.path.join(_HERE, "libfss_mi355.so")
+_lib: Optional[C.CDLL] = None
+
+EXPORTS = ("fss_cmp_key_bytes", "fss_eq_key_bytes", "fss_cmp_gen", "fss_cmp_eval", "fss_eq_gen", "fss_eq_eval",
+           "fss_strerror", "fss_last_hip_error")
+
+HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
+class FssError(RuntimeError):
+    def __init__(self, code: int, text: str, hip_error: int = 0):
+        super().__init__(f"fss error {code}: {text}" + (f" (hipError_t {hip_error})" if hip_error else ""))
+        self.code = code
+        self.hip_error = hip_error
+
+
+def library_path() -> str:
+    return _SO
+
+
+def build(verbose: bool = False) -> str:
+    """Compile the HIP sources for gfx950 into libfss_mi355.so (in-tree)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc] + HIPCC_FLAGS + [os.path.join(_CSRC, "fss_kernels.hip"), "-o", _SO]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if verbose or res.returncode != 0:
+        print(res.stdout)
+        print(res.stderr)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed building libfss_mi355.so")
+    global _lib
+    _lib = None
+    return _SO
+
+
+def lib() -> C.CDLL:
+    """The loaded library.  Raises if it has not been built: there is no fallback path."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_SO):
+            raise FileNotFoundError(
+                f"{_SO} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+        L = C.CDLL(_SO)
+        vp, sz, i = C.c_void_p, C.c_size_t, C.c_int
+        for name in ("fss_cmp_key_bytes", "fss_eq_key_bytes"):
+            getattr(L, name).argtypes = [i, sz]
+            getattr(L, name).restype = sz
+        for name in ("fss_cmp_gen", "fss_eq_gen"):
+            getattr(L, name).argtypes = [i, sz, vp, vp, vp, vp, vp, vp, vp]
+            getattr(L, name).restype = i
+        for name in ("fss_cmp_eval", "fss_eq_eval"):
+            getattr(L, name).argtypes = [i, i, sz, vp, vp, vp, vp]
+            getattr(L, name).restype = i
+        L.fss_strerror.argtypes = [i]
+        L.fss_strerror.restype = C.c_char_p
+        L.fss_last_hip_error.argtypes = []
+        L.fss_last_hip_error.restype = i
+        _lib = L
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        L = lib()
+        raise FssError(rc, L.fss_strerror(rc).decode(), L.fss_last_hip_error())
+
+
+def cmp_key_bytes(n: int, batch: int) -> int:
+    return int(lib().fss_cmp_key_bytes(n, batch))
+
+
+def eq_key_bytes(n: int, batch: int) -> int:
+    return int(lib().fss_eq_key_bytes(n, batch))
+
+
+def _ptr(t) -> int:
+    return 0 if t is None else int(t.data_ptr())
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return stream
+    return int(stream.cuda_stream)
+
+
+def _gen(fn, n, batch, d_alpha, d_alpha_r, d_seed0, d_seed1, d_key0, d_key1, stream):
+    _check(fn(n, batch, _ptr(d_alpha), _ptr(d_alpha_r), _ptr(d_seed0), _ptr(d_seed1), _ptr(d_key0), _ptr(d_key1),
+              _stream(stream)))
+
+
+def cmp_gen(n: int, batch: int, d_alpha, d_alpha_r, d_seed0, d_seed1, d_key0, d_key1, stream=None) -> None:
+    """fss_cmp_gen: device tensors in, both parties' key buffers (uint8 device tensors) out."""
+    _gen(lib().fss_cmp_gen, n, batch, d_alpha, d_alpha_r, d_seed0, d_seed1, d_key0, d_key1, stream)
+
+
+def eq_gen(n: int, batch: int, d_alpha, d_alpha_r, d_seed0, d_seed1, d_key0, d_key1, stream=None) -> None:
+    _gen(lib().fss_eq_gen, n, batch, d_alpha, d_alpha_r, d_seed0, d_seed1, d_key0, d_key1, stream)
+
+
+def cmp_eval(party: int, n: int, batch: int, d_key, d_x, d_out, stream=None) -> None:
+    _check(lib().fss_cmp_eval(party, n, batch, _ptr(d_key), _ptr(d_x), _ptr(d_out), _stream(stream)))
+
+
+def eq_eval(party: int, n: int, batch: int, d_key, d_x, d_out, stream=None) -> None:
+    _check(lib().fss_eq_eval(party, n, batch, _ptr(d_key), _ptr(d_x), _ptr(d_out), _stream(stream)))

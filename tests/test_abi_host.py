@@ -1,0 +1,95 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+declared in include/fss.h, sizes its key buffers like the paper's closed form, and rejects
+bad arguments before touching the device."""
+import os
+import re
+
+import pytest
+
+import paper_2006_04593_amd as fss
+from paper_2006_04593_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(fss.library_path()):
+        fss.build()
+    return fss.lib()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "fss.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fss_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert set(names) == set(binding.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_key_bytes(lib):
+    assert fss.cmp_key_bytes(32, 64) == 808 * 64
+    assert fss.eq_key_bytes(32, 64) == 544 * 64
+    assert fss.cmp_key_bytes(32, 65) == 808 * 128          # padded to a wavefront
+    assert fss.cmp_key_bytes(32, 1 << 22) == 808 << 22     # the paper's 808 bytes per element
+    assert fss.cmp_key_bytes(8, 64) == 64 * (4 + 16 + 16 + 8 * 24 + 4)
+    assert fss.eq_key_bytes(12, 64) == 64 * (4 + 16 + 8 + 12 * 16 + 4)
+    for n in (0, -1, 33):
+        assert fss.cmp_key_bytes(n, 64) == 0 and fss.eq_key_bytes(n, 64) == 0
+    assert fss.cmp_key_bytes(32, 0) == 0
+
+
+def test_key_sizes_agree_with_the_oracle_layout(lib):
+    import oracle
+    for n in (1, 8, 12, 32):
+        for batch in (1, 64, 1000):
+            assert fss.cmp_key_bytes(n, batch) == oracle.key_bytes("cmp", n, batch)
+            assert fss.eq_key_bytes(n, batch) == oracle.key_bytes("eq", n, batch)
+
+
+def test_bad_arguments_are_rejected_on_the_host(lib):
+    A = 0x10000                                       # any aligned non-null address; never dereferenced
+    for f in (lib.fss_cmp_eval, lib.fss_eq_eval):
+        assert f(2, 32, 8, A, A, A, None) == -1       # party
+        assert f(-1, 32, 8, A, A, A, None) == -1
+        assert f(0, 0, 8, A, A, A, None) == -1        # n
+        assert f(0, 33, 8, A, A, A, None) == -1
+        assert f(0, 32, 8, None, A, A, None) == -1    # NULL
+        assert f(0, 32, 8, A, None, A, None) == -1
+        assert f(0, 32, 8, A, A, None, None) == -1
+        assert f(0, 32, 8, A + 16, A, A, None) == -1  # key buffer alignment
+        assert f(0, 32, 8, A, A + 2, A, None) == -1
+        assert f(0, 32, 0, None, None, None, None) == 0   # empty batch is a no-op
+        assert f(0, 33, 0, None, None, None, None) == -1  # ... but n is still checked
+    for f in (lib.fss_cmp_gen, lib.fss_eq_gen):
+        B = A + (1 << 20)
+        assert f(0, 8, A, A, A, A, A, B, None) == -1
+        assert f(32, 8, None, A, A, A, A, B, None) == -1
+        assert f(32, 8, A, A, A + 4, A, A, B, None) == -1     # seeds need 16-byte alignment
+        assert f(32, 8, A, A, A, A, A, A, None) == -1         # overlapping key buffers
+        assert f(32, 8, A, A, A, A, A, A + 256, None) == -1
+        assert f(32, 0, None, None, None, None, None, None, None) == 0
+
+
+def test_strerror(lib):
+    assert lib.fss_strerror(0) == b"success"
+    for code in (-1, -2, -3, 17):
+        assert len(lib.fss_strerror(code)) > 0
+
+
+def test_binding_raises_with_the_code():
+    with pytest.raises(fss.FssError) as e:
+        fss.cmp_eval(5, 32, 4, None, None, None, stream=0)
+    assert e.value.code == -1
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_SO", str(tmp_path / "absent.so"))
+    with pytest.raises(FileNotFoundError):
+        fss.cmp_key_bytes(32, 64)

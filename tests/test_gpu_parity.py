@@ -1,0 +1,246 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle --
+bit-exact keys (KeyGen) and shares (Eval) on the same seeded inputs, plus cross-pairing
+(oracle keys -> GPU Eval, GPU keys -> oracle Eval)."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2006_04593_amd as fss
+from paper_2006_04593_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def dev():
+    return torch.device("cuda:0")
+
+
+def to_dev(a: np.ndarray):
+    if a.dtype == np.uint32:
+        a = a.view(np.int32)
+    return torch.from_numpy(np.ascontiguousarray(a)).to(dev())
+
+
+def u32(t) -> np.ndarray:
+    return t.cpu().numpy().view(np.uint32)
+
+
+def key_bytes(kind, n, batch):
+    return (fss.cmp_key_bytes if kind == "cmp" else fss.eq_key_bytes)(n, batch)
+
+
+def gpu_gen(kind, n, g: W.GenInputs):
+    nbytes = key_bytes(kind, n, g.batch)
+    k0 = torch.full((nbytes,), 0xA5, dtype=torch.uint8, device=dev())   # poison: Gen must write every byte
+    k1 = torch.full((nbytes,), 0x5A, dtype=torch.uint8, device=dev())
+    f = fss.cmp_gen if kind == "cmp" else fss.eq_gen
+    f(n, g.batch, to_dev(g.alpha), to_dev(g.r), to_dev(g.seed0), to_dev(g.seed1), k0, k1)
+    torch.cuda.synchronize()
+    return k0, k1
+
+
+def gpu_eval(kind, party, n, key, x: np.ndarray):
+    batch = x.shape[0]
+    out = torch.full((batch,), -1, dtype=torch.int32, device=dev())
+    f = fss.cmp_eval if kind == "cmp" else fss.eq_eval
+    f(party, n, batch, key, to_dev(x), out)
+    torch.cuda.synchronize()
+    return u32(out)
+
+
+def truth(kind, x, alpha):
+    x = x.astype(np.uint64); alpha = alpha.astype(np.uint64)
+    return ((x <= alpha) if kind == "cmp" else (x == alpha)).astype(np.uint32)
+
+
+def check_full(kind, n, g: W.GenInputs, x: np.ndarray):
+    print(f"case kind={kind} n={n} batch={g.batch}", flush=True)
+    k0, k1 = gpu_gen(kind, n, g)
+    r0, r1 = oracle.gen(kind, n, g.alpha, g.r, g.seed0, g.seed1)
+    assert np.array_equal(k0.cpu().numpy(), r0), "party-0 key differs from the oracle's"
+    assert np.array_equal(k1.cpu().numpy(), r1), "party-1 key differs from the oracle's"
+    o0, o1 = gpu_eval(kind, 0, n, k0, x), gpu_eval(kind, 1, n, k1, x)
+    assert np.array_equal(o0, oracle.eval_(kind, 0, n, r0, x))
+    assert np.array_equal(o1, oracle.eval_(kind, 1, n, r1, x))
+    assert np.array_equal((o0 + o1) & np.uint32(W.ring_mask(n)), truth(kind, x & np.uint32(W.ring_mask(n)), g.alpha & np.uint32(W.ring_mask(n))))
+
+
+# sizes: below one wavefront, ragged tails, several 1024-element workgroup tiles
+@pytest.mark.parametrize("kind", ["cmp", "eq"])
+@pytest.mark.parametrize("n,batch", [(32, 1), (32, 63), (32, 64), (32, 65), (32, 1000), (32, 1024), (32, 5000),
+                                     (32, 16384), (1, 100), (2, 129), (8, 300), (12, 2049), (16, 4097), (31, 777)])
+def test_gen_and_eval_match_oracle(kind, n, batch):
+    w = W.uniform_workload(kind, n, batch, seed=1000 * n + batch)
+    x = w.x.copy()
+    x[::3] = w.gen.alpha[::3]                      # equality hits / the x = alpha boundary
+    x[1::7] = w.gen.alpha[1::7] + np.uint32(1)
+    x &= np.uint32(W.ring_mask(n))
+    check_full(kind, n, w.gen, x)
+
+
+@pytest.mark.parametrize("kind", ["cmp", "eq"])
+def test_edge_offsets_and_inputs(kind):
+    n = 32
+    edges = W.edge_inputs(n)
+    alpha = np.repeat(edges, len(edges))
+    x = np.tile(edges, len(edges))
+    g = W.gen_inputs(np.random.default_rng(12), n, len(alpha), alpha=alpha)
+    check_full(kind, n, g, x)
+
+
+@pytest.mark.parametrize("kind", ["cmp", "eq"])
+@pytest.mark.parametrize("n", [8, 12])
+def test_every_input_of_a_small_ring(kind, n):
+    """All 2^n inputs against each of a few keys: the batch holds one key repeated 2^n times."""
+    rng = np.random.default_rng(800 + n)
+    for a in [0, W.ring_mask(n), int(rng.integers(0, 1 << n))]:
+        size = 1 << n
+        one = W.gen_inputs(rng, n, 1, alpha=np.array([a], dtype=np.uint32))
+        g = W.GenInputs(n=n, alpha=np.repeat(one.alpha, size), r=np.repeat(one.r, size),
+                        seed0=np.repeat(one.seed0, size, axis=0), seed1=np.repeat(one.seed1, size, axis=0))
+        x = np.arange(size, dtype=np.uint32)
+        k0, k1 = gpu_gen(kind, n, g)
+        o0, o1 = gpu_eval(kind, 0, n, k0, x), gpu_eval(kind, 1, n, k1, x)
+        r0, r1 = oracle.gen(kind, n, one.alpha, one.r, one.seed0, one.seed1)
+        assert np.array_equal(o0, oracle.eval_all_x(kind, 0, n, 1, r0, 0))
+        assert np.array_equal(o1, oracle.eval_all_x(kind, 1, n, 1, r1, 0))
+        assert np.array_equal((o0 + o1) & np.uint32(W.ring_mask(n)), truth(kind, x, g.alpha))
+
+
+@pytest.mark.parametrize("kind", ["cmp", "eq"])
+def test_cross_pairing(kind):
+    """Keys made by one side evaluate identically on the other."""
+    n, batch = 32, 3333
+    w = W.uniform_workload(kind, n, batch, seed=99)
+    g, x = w.gen, w.x
+    r0, r1 = oracle.gen(kind, n, g.alpha, g.r, g.seed0, g.seed1)
+    # oracle keys -> GPU Eval
+    o0 = gpu_eval(kind, 0, n, torch.from_numpy(r0).to(dev()), x)
+    o1 = gpu_eval(kind, 1, n, torch.from_numpy(r1).to(dev()), x)
+    assert np.array_equal(o0, oracle.eval_(kind, 0, n, r0, x)) and np.array_equal(o1, oracle.eval_(kind, 1, n, r1, x))
+    # GPU keys -> oracle Eval
+    k0, k1 = gpu_gen(kind, n, g)
+    c0 = oracle.eval_(kind, 0, n, k0.cpu().numpy(), x)
+    c1 = oracle.eval_(kind, 1, n, k1.cpu().numpy(), x)
+    assert np.array_equal(c0 + c1, truth(kind, x, g.alpha))
+
+
+def test_values_above_the_ring_are_reduced():
+    n, batch = 12, 500
+    w = W.uniform_workload("cmp", n, batch, seed=5)
+    g = w.gen
+    hi = W.GenInputs(n=n, alpha=g.alpha | np.uint32(0xABC000), r=g.r | np.uint32(0x1000), seed0=g.seed0 | np.uint8(1), seed1=g.seed1)
+    k0, k1 = gpu_gen("cmp", n, hi)
+    r0, r1 = oracle.gen("cmp", n, g.alpha, g.r, g.seed0, g.seed1)
+    assert np.array_equal(k0.cpu().numpy(), r0) and np.array_equal(k1.cpu().numpy(), r1)
+    assert np.array_equal(gpu_eval("cmp", 0, n, k0, w.x | np.uint32(0xFFFFF000)), oracle.eval_("cmp", 0, n, r0, w.x))
+
+
+def test_empty_batch_is_a_noop_and_errors_raise():
+    fss.cmp_eval(0, 32, 0, None, None, None)
+    fss.eq_gen(32, 0, None, None, None, None, None, None)
+    with pytest.raises(fss.FssError):
+        fss.cmp_eval(3, 32, 0, None, None, None)
+    torch.cuda.synchronize()
+
+
+def test_non_default_stream():
+    n, batch = 32, 2048
+    w = W.uniform_workload("eq", n, batch, seed=31)
+    g = w.gen
+    st = torch.cuda.Stream()
+    nbytes = fss.eq_key_bytes(n, batch)
+    k0 = torch.zeros(nbytes, dtype=torch.uint8, device=dev())
+    k1 = torch.zeros(nbytes, dtype=torch.uint8, device=dev())
+    out = torch.zeros(batch, dtype=torch.int32, device=dev())
+    args = [to_dev(a) for a in (g.alpha, g.r, g.seed0, g.seed1)]
+    xd = to_dev(w.x)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(st):
+        fss.eq_gen(n, batch, *args, k0, k1, stream=st)
+        fss.eq_eval(1, n, batch, k1, xd, out, stream=st)
+    st.synchronize()
+    r0, r1 = oracle.gen("eq", n, g.alpha, g.r, g.seed0, g.seed1)
+    assert np.array_equal(u32(out), oracle.eval_("eq", 1, n, r1, w.x))
+
+
+# ---------------------------------------------------------------- benchmark configurations
+
+def check_sampled(kind, n, g: W.GenInputs, x: np.ndarray, samples: int, seed: int):
+    """Full-size run on the GPU; the oracle recomputes a seeded sample of elements (keys of
+    an element depend on that element's arguments only) and the reconstruction identity is
+    checked on every element."""
+    print(f"case kind={kind} n={n} batch={g.batch} sampled={samples}", flush=True)
+    k0, k1 = gpu_gen(kind, n, g)
+    o0, o1 = gpu_eval(kind, 0, n, k0, x), gpu_eval(kind, 1, n, k1, x)
+    assert np.array_equal(o0 + o1, truth(kind, x, g.alpha))
+    idx = np.sort(np.random.default_rng(seed).choice(g.batch, size=samples, replace=False))
+    idx[0], idx[-1] = 0, g.batch - 1
+    sub = W.GenInputs(n=n, alpha=g.alpha[idx], r=g.r[idx], seed0=g.seed0[idx], seed1=g.seed1[idx])
+    r0, r1 = oracle.gen(kind, n, sub.alpha, sub.r, sub.seed0, sub.seed1)
+    assert np.array_equal(o0[idx], oracle.eval_(kind, 0, n, r0, x[idx]))
+    assert np.array_equal(o1[idx], oracle.eval_(kind, 1, n, r1, x[idx]))
+    # key planes of the sampled elements, byte for byte
+    for kd, rk in ((k0, r0), (k1, r1)):
+        full = oracle.split_key(kind, n, g.batch, kd.cpu().numpy())
+        part = oracle.split_key(kind, n, samples, rk)
+        for plane in ("alpha_share", "seed", "ctrl", "last"):
+            assert np.array_equal(full[plane][idx], part[plane][:samples]), plane
+        planes = ("s_cw", "sigma_cw", "leaf") if kind == "cmp" else ("s_cw",)
+        for plane in planes:
+            assert np.array_equal(full[plane][:, idx], part[plane][:, :samples]), plane
+        del full
+    return o0, o1
+
+
+def test_config1_comparison_16k():
+    w = W.config_workload(1)
+    check_full("cmp", 32, w.gen, w.x)
+
+
+def test_config2_equality_1m():
+    w = W.config_workload(2)
+    o0, o1 = check_sampled("eq", 32, w.gen, w.x, samples=4096, seed=2)
+    assert np.array_equal((o0 + o1).astype(bool), w.extra["hit"] | (w.x == w.gen.alpha))
+
+
+def test_config3_relu_layer():
+    w = W.config_workload(3)
+    o0, o1 = check_sampled("cmp", 32, w.gen, w.x, samples=4096, seed=3)
+    # Sign protocol: disagrees with 1{y <= 0} only on the rare wrap-around (|y| / 2^32 each)
+    assert ((o0 + o1) != (w.extra["y"] <= 0)).sum() <= 8
+
+
+def test_config4_maxpool_dependent_rounds():
+    """8 dependent comparison rounds of 200,704 elements: running maximum over the nine
+    taps of each 3x3 window; the reveal between rounds is done in the clear by the test."""
+    n = 32
+    taps = W.maxpool_taps(W.BASE_SEED + 4)
+    batch = taps.shape[1]
+    assert batch == 64 * 56 * 56
+    m = taps[0].copy()
+    rng = np.random.default_rng(44)
+    idx = np.sort(rng.choice(batch, size=1024, replace=False))
+    for rnd in range(1, W.MAXPOOL_ROUNDS + 1):
+        g = W.maxpool_round_keys(W.BASE_SEED + 4, rnd, batch)
+        d = m - taps[rnd]                                   # m <= w  <=>  d <= 0
+        x = ((d + g.alpha.astype(np.int64)) & 0xFFFFFFFF).astype(np.uint32)
+        k0, k1 = gpu_gen("cmp", n, g)
+        o0, o1 = gpu_eval("cmp", 0, n, k0, x), gpu_eval("cmp", 1, n, k1, x)
+        c = o0 + o1
+        assert np.array_equal(c, truth("cmp", x, g.alpha))
+        sub = W.GenInputs(n=n, alpha=g.alpha[idx], r=g.r[idx], seed0=g.seed0[idx], seed1=g.seed1[idx])
+        r0, r1 = oracle.gen("cmp", n, sub.alpha, sub.r, sub.seed0, sub.seed1)
+        assert np.array_equal(o0[idx], oracle.eval_("cmp", 0, n, r0, x[idx]))
+        assert np.array_equal(o1[idx], oracle.eval_("cmp", 1, n, r1, x[idx]))
+        m = np.where(c == 1, taps[rnd], m)
+        del k0, k1
+    # wrap-around failures are ~|d|/2^32 per comparison: allow a handful of windows to differ
+    assert (m != taps.max(axis=0)).sum() <= 8
+
+
+def test_config5_large_batch_sampled():
+    w = W.config_workload(5)
+    check_sampled("cmp", 32, w.gen, w.x, samples=8192, seed=5)
