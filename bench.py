@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Benchmark of the FSS hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic batch: comparison KeyGen for B
+elements, then both parties' Eval.  The workload is the large-batch configuration
+(B = 2^22, n = 32, uniform alpha and x), with every input and both key buffers resident in
+HBM before the timed region.  Prints ONE JSON line.
+
+  value      comparison evaluations per second per party = B / mean duration of one Eval launch
+  roofline   the dominant kernel (comparison Eval) against the 32-bit integer/bitwise VALU peak
+  cpu_baseline  the plain-C oracle timed on this host's cores on a bounded sample
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# ---- work model of the comparison Eval kernel ("Rooflines") -------------
+N_BITS = 32
+AES_BLOCKS_PER_EVAL = 2 * N_BITS            # one child block + one sigma/tau block per level
+VALU_OPS_PER_BLOCK = 320                    # static VALU instructions per AES block in the kernel's ISA
+TREE_OPS_PER_LEVEL = 30                     # correction-word gating, selects, accumulate
+LANE_OPS_PER_EVAL = AES_BLOCKS_PER_EVAL * VALU_OPS_PER_BLOCK + N_BITS * TREE_OPS_PER_LEVEL
+BYTES_PER_EVAL = 804 + 4 + 4                # key planes read by Eval + x + out
+PEAK_LANE_TOPS = 256 * 64 * 2.4e9 / 1e12    # 256 CUs x 64 lanes x 2.4 GHz = 39.3 T 32-bit lane-ops/s
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(sample: int):
+    """The oracle as it stands, on the host cores, on the first `sample` elements of the workload."""
+    import numpy as np
+    import oracle
+    from paper_2006_04593_amd import workloads as W
+    threads = oracle.set_threads(0)
+    w = W.uniform_workload("cmp", N_BITS, sample, seed=W.BASE_SEED + 5)
+    g = w.gen
+    t0 = time.perf_counter()
+    k0, k1 = oracle.gen("cmp", N_BITS, g.alpha, g.r, g.seed0, g.seed1)
+    t1 = time.perf_counter()
+    o0 = oracle.eval_("cmp", 0, N_BITS, k0, w.x)
+    t2 = time.perf_counter()
+    o1 = oracle.eval_("cmp", 1, N_BITS, k1, w.x)
+    t3 = time.perf_counter()
+    assert np.array_equal(o0 + o1, (w.x <= g.alpha).astype(np.uint32))
+    per_party = ((t2 - t1) + (t3 - t2)) / 2
+    return {
+        "value": sample / per_party,
+        "unit": "evals/s/party",
+        "cores": threads,
+        "kind": "oracle",
+        "sample": f"first-seed {sample} elements of the same workload: cmp Gen {t1 - t0:.2f} s, "
+                  f"Eval party0 {t2 - t1:.2f} s, party1 {t3 - t2:.2f} s",
+        "gen_pairs_per_s": sample / (t1 - t0),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--batch", type=int, default=1 << 22, help="elements per step (default: the 2^22 configuration)")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 18, help="elements for the oracle timing; 0 skips it")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this path runs on ONE GPU (elements are independent; more GPUs would only shard the "
+              "batch with no exchange, see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2006_04593_amd as fss
+    from paper_2006_04593_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    B, n = args.batch, N_BITS
+    w = W.uniform_workload("cmp", n, B, seed=W.BASE_SEED + 5, name="config5")
+    g = w.gen
+    d_alpha, d_r, d_x = (torch.from_numpy(a.view(np.int32)).to(dev) for a in (g.alpha, g.r, w.x))
+    d_s0, d_s1 = torch.from_numpy(g.seed0).to(dev), torch.from_numpy(g.seed1).to(dev)
+    nbytes = fss.cmp_key_bytes(n, B)
+    k0 = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    k1 = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    o0 = torch.empty(B, dtype=torch.int32, device=dev)
+    o1 = torch.empty(B, dtype=torch.int32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    def step(marks=None):
+        if marks is not None:
+            e = [ev() for _ in range(4)]
+            e[0].record(stream)
+        fss.cmp_gen(n, B, d_alpha, d_r, d_s0, d_s1, k0, k1, stream=stream)
+        if marks is not None:
+            e[1].record(stream)
+        fss.cmp_eval(0, n, B, k0, d_x, o0, stream=stream)
+        if marks is not None:
+            e[2].record(stream)
+        fss.cmp_eval(1, n, B, k1, d_x, o1, stream=stream)
+        if marks is not None:
+            e[3].record(stream)
+            marks.append(e)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    marks = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(marks)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    # correctness of what was just timed: reconstruction on every element
+    rec = (o0 + o1).cpu().numpy().view(np.uint32)
+    assert np.array_equal(rec, (w.x <= g.alpha).astype(np.uint32)), "reconstruction failed"
+
+    gen_ms = [e[0].elapsed_time(e[1]) for e in marks]
+    ev_ms = [e[1].elapsed_time(e[2]) for e in marks] + [e[2].elapsed_time(e[3]) for e in marks]
+    eval_ms = sum(ev_ms) / len(ev_ms)
+    gen_mean = sum(gen_ms) / len(gen_ms)
+    evals_per_s = B / (eval_ms * 1e-3)
+
+    achieved_tops = B * LANE_OPS_PER_EVAL / (eval_ms * 1e-3) / 1e12
+    out = {
+        "metric": "FSS comparison evals/sec per party (n=32, lambda=128)",
+        "value": evals_per_s,
+        "unit": "evals/s/party",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32",
+        "data": "synthetic",
+        "config": {"workload": f"large batch: cmp Gen of {B} keys + both parties' Eval, n=32, uniform alpha and x, "
+                               "SoA keys resident in HBM", "batch": B, "n": n, "lambda": 128},
+        "eval_ms": eval_ms,
+        "eval_ms_min": min(ev_ms),
+        "gen_ms": gen_mean,
+        "gen_key_pairs_per_s": B / (gen_mean * 1e-3),
+        "step_evals_per_s_incl_gen": 2 * B / (wall / args.steps),
+        "roofline": {
+            "bound": "alu",
+            "kernel": "eval_kernel<cmp>",
+            "achieved": achieved_tops,
+            "peak": PEAK_LANE_TOPS,
+            "unit": "T 32-bit lane-ops/s",
+            "frac": achieved_tops / PEAK_LANE_TOPS,
+            "traffic": None,
+            "lane_ops_per_eval": LANE_OPS_PER_EVAL,
+            "hbm_frac": BYTES_PER_EVAL * evals_per_s / 1e9 / PEAK_HBM_GBS,
+        },
+    }
+    if args.cpu_sample > 0:
+        out["cpu_baseline"] = cpu_baseline(args.cpu_sample)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -53,6 +53,11 @@ def lib() -> C.CDLL:
         if not os.path.exists(_SO):
             raise FileNotFoundError(
                 f"{_SO} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+        # PyTorch ships its own copy of the HIP runtime (same soname).  Importing torch first
+        # makes the loader bind this library to that copy, so both see the same device
+        # context, streams and allocations; loaded the other way round the process would
+        # hold two runtimes and every launch here would fail with "no device".
+        import torch  # noqa: F401
         L = C.CDLL(_SO)
         vp, sz, i = C.c_void_p, C.c_size_t, C.c_int
         for name in ("fss_cmp_key_bytes", "fss_eq_key_bytes"):

@@ -131,7 +131,9 @@ def test_values_above_the_ring_are_reduced():
     n, batch = 12, 500
     w = W.uniform_workload("cmp", n, batch, seed=5)
     g = w.gen
-    hi = W.GenInputs(n=n, alpha=g.alpha | np.uint32(0xABC000), r=g.r | np.uint32(0x1000), seed0=g.seed0 | np.uint8(1), seed1=g.seed1)
+    flip = np.zeros_like(g.seed0)
+    flip[:, 0] = 1                                  # the control-bit position of a seed block is ignored
+    hi = W.GenInputs(n=n, alpha=g.alpha | np.uint32(0xABC000), r=g.r | np.uint32(0x1000), seed0=g.seed0 ^ flip, seed1=g.seed1)
     k0, k1 = gpu_gen("cmp", n, hi)
     r0, r1 = oracle.gen("cmp", n, g.alpha, g.r, g.seed0, g.seed1)
     assert np.array_equal(k0.cpu().numpy(), r0) and np.array_equal(k1.cpu().numpy(), r1)
