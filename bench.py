@@ -66,6 +66,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--batch", type=int, default=1 << 22, help="elements per step (default: the 2^22 configuration)")
     ap.add_argument("--cpu-sample", type=int, default=1 << 18, help="elements for the oracle timing; 0 skips it")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also launch one plain elementwise copy over 1 GiB, so that a rocprofv3 --pmc run of this "
+                         "command holds the counter's reading for a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path runs on ONE GPU (elements are independent; more GPUs would only shard the "
@@ -110,6 +113,13 @@ def main():
         if marks is not None:
             e[3].record(stream)
             marks.append(e)
+
+    if args.pmc_calibration:
+        src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

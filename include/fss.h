@@ -15,7 +15,8 @@
  * General rules
  *   - Every pointer whose name starts with d_ is DEVICE memory on the current HIP device,
  *     owned by the caller before, during and after the call.  The library allocates no
- *     device memory, keeps no pointer, and holds no mutable state between calls.
+ *     device memory, keeps no pointer, and holds no state between calls that affects
+ *     results (it remembers per device that its kernels were configured).
  *   - Calls only ENQUEUE work on `stream` (a hipStream_t; NULL = the default stream) and
  *     return without waiting; the caller synchronises.  Buffers must stay valid until the
  *     enqueued work has finished.
@@ -45,8 +46,9 @@
  *     s_CW [n][Bp][16] | CW_last [Bp] u32                = 544 bytes per element at n = 32.
  *
  *   The correction-word planes of k_0 and k_1 are identical; the keys differ in seed and
- *   alpha_share.  Elements batch..Bp-1 of every plane are padding (KeyGen leaves them
- *   untouched; Eval never reads them).
+ *   alpha_share.  Elements batch..Bp-1 of every plane are padding (KeyGen writes them
+ *   as zeros, so a key buffer is a deterministic function of the arguments; Eval never
+ *   reads them).
  *
  * Conventions the paper leaves open, fixed by this library:
  *   - block = 16 bytes in FIPS-197 order; control bit t = bit 0 of byte 0; a seed is a block
