@@ -100,80 +100,75 @@ __device__ __forceinline__ uint32_t bitop3(uint32_t a, uint32_t b, uint32_t c)
 // m must be 0 or ~0: all bits of x1 where m is set, else of x0
 __device__ __forceinline__ uint32_t pick32(uint32_t m, uint32_t x1, uint32_t x0) { return bitop3<kSelect>(m, x1, x0); }
 
-// acc ^ round-key word `idx` of block key M.  M = 0..2: that PRG key for every lane.
-// M = -1: PRG key 1 for lanes with pick = 0 and PRG key 2 for lanes with pick = ~0, as
-// key_1 ^ (pick & (key_1 ^ key_2)), so that both constants stay in scalar registers.
-template <int M>
-__device__ __forceinline__ uint32_t add_round_key(uint32_t acc, uint32_t extra, int idx, uint32_t pick)
+// acc ^ extra ^ round-key word `idx` of PRG key `m`.  m = 0..2: that key for every lane.
+// m = -1: PRG key 1 for lanes with pick = 0 and PRG key 2 for lanes with pick = ~0, formed as
+// key_1 ^ (pick & (key_1 ^ key_2)) so that both constants stay in scalar registers.
+// (m is a compile-time constant after unrolling; the branches fold away.)
+__device__ __forceinline__ uint32_t add_round_key(int m, uint32_t acc, uint32_t extra, int idx, uint32_t pick)
 {
-    if constexpr (M >= 0) {
-        (void)pick;
-        return bitop3<kXor3>(acc, extra, kAes.rk[M][idx]);
-    } else {
-        uint32_t v = bitop3<kXor3>(acc, extra, kAes.rk[0][idx]);
-        return bitop3<kXorAnd>(v, pick, kAes.rk[0][idx] ^ kAes.rk[1][idx]);
-    }
+    if (m >= 0) return bitop3<kXor3>(acc, extra, kAes.rk[m][idx]);
+    uint32_t v = bitop3<kXor3>(acc, extra, kAes.rk[0][idx]);
+    return bitop3<kXorAnd>(v, pick, kAes.rk[0][idx] ^ kAes.rk[1][idx]);
 }
 
-template <int M0, int M1, int M2>
-__device__ __forceinline__ uint32_t add_round_key_b(int b, uint32_t acc, uint32_t extra, int idx, uint32_t pick)
+// The four table lookups that feed output column c of the next round.  lk[r] is the
+// contribution of the row-r byte (ShiftRows: it comes from state column c + r).  Rounds
+// 1..9 read table r; the last round reads table r + 2, whose byte r is S(v).
+template <bool LAST>
+__device__ __forceinline__ void issue_column(uint32_t *lk, const uint32_t (&st)[4], int c, LaneBase L)
 {
-    return b == 0 ? add_round_key<M0>(acc, extra, idx, pick)
-         : b == 1 ? add_round_key<M1>(acc, extra, idx, pick) : add_round_key<M2>(acc, extra, idx, pick);
+    const uint32_t b01 = LAST ? L.b : L.a;   // rows 0,1: tables 0,1 (2,3 in the last round)
+    const uint32_t b23 = LAST ? L.a : L.b;   // rows 2,3: tables 2,3 (0,1 in the last round)
+    lk[0] = lds_load(entry_addr<0>(st[c], b01));
+    lk[1] = lds_load(entry_addr<1>(st[(c + 1) & 3], b01) + kOddTable);
+    lk[2] = lds_load(entry_addr<2>(st[(c + 2) & 3], b23));
+    lk[3] = lds_load(entry_addr<3>(st[(c + 3) & 3], b23) + kOddTable);
 }
 
-// One full AES-128 encryption of NB blocks of the same input `seed` under keys M0..M2,
-// followed by the Matyas-Meyer-Oseas feed-forward: out[b] = E_{k_b}(seed) ^ seed.
-// `pick` (0 or ~0 per lane) is only read by blocks whose key is -1.
-template <int M0, int M1, int M2, int NB>
-__device__ __forceinline__ void aes_mmo(uint32_t (&out)[NB][4], const uint32_t (&seed)[4], uint32_t pick, LaneBase L)
+// NB independent AES-128 encryptions per lane, each followed by the Matyas-Meyer-Oseas
+// feed-forward: out[b] = E_{key M_b}(seed[b]) ^ seed[b].  pick[b] (0 or ~0 per lane) is only
+// read by blocks whose key is -1.
+//
+// A wavefront can keep 16 LDS instructions in flight and a round of one block is exactly 16
+// lookups, so the unit of work is a block-round: issue its 16 lookups, then combine.  The
+// combine starts with the LAST column, so one wait covers the whole round (fewer
+// instructions on the wave's in-order issue path than a wait per column).
+template <int... M>
+__device__ __forceinline__ void aes_mmo(uint32_t (&out)[sizeof...(M)][4], const uint32_t (&seed)[sizeof...(M)][4],
+                                        const uint32_t (&pick)[sizeof...(M)], LaneBase L)
 {
-    static_assert(NB >= 1 && NB <= 3, "1..3 blocks per call");
+    constexpr int NB = sizeof...(M);
+    constexpr int keys[NB] = { M... };
     uint32_t st[NB][4];
 #pragma unroll
     for (int b = 0; b < NB; b++)
 #pragma unroll
-        for (int c = 0; c < 4; c++) st[b][c] = add_round_key_b<M0, M1, M2>(b, seed[c], 0u, c, pick);
-#pragma unroll
-    for (int r = 1; r <= 9; r++) {
-        uint32_t l[NB][4][4];
-#pragma unroll
+        for (int c = 0; c < 4; c++) st[b][c] = add_round_key(keys[b], seed[b][c], 0u, c, pick[b]);
+#pragma clang loop unroll(full)
+    for (int r = 1; r <= 10; r++) {
+#pragma clang loop unroll(full)
         for (int b = 0; b < NB; b++) {
+            uint32_t lk[16];
 #pragma unroll
             for (int c = 0; c < 4; c++) {
-                l[b][c][0] = lds_load(entry_addr<0>(st[b][c], L.a));
-                l[b][c][1] = lds_load(entry_addr<1>(st[b][(c + 1) & 3], L.a) + kOddTable);
-                l[b][c][2] = lds_load(entry_addr<2>(st[b][(c + 2) & 3], L.b));
-                l[b][c][3] = lds_load(entry_addr<3>(st[b][(c + 3) & 3], L.b) + kOddTable);
+                if (r < 10) issue_column<false>(&lk[4 * c], st[b], c, L);
+                else issue_column<true>(&lk[4 * c], st[b], c, L);
             }
-        }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int b = 0; b < NB; b++)
-#pragma unroll
-            for (int c = 0; c < 4; c++)
-                st[b][c] = add_round_key_b<M0, M1, M2>(b, bitop3<kXor3>(l[b][c][0], l[b][c][1], l[b][c][2]),
-                                                       l[b][c][3], 4 * r + c, pick);
-    }
-    // last round: SubBytes + ShiftRows only.  S(v) sits in byte 0 of te_2, byte 1 of te_3,
-    // byte 2 of te_0 and byte 3 of te_1.
-    uint32_t l[NB][4][4];
-#pragma unroll
-    for (int b = 0; b < NB; b++) {
-#pragma unroll
-        for (int c = 0; c < 4; c++) {
-            l[b][c][0] = lds_load(entry_addr<0>(st[b][c], L.b));                          // te_2
-            l[b][c][1] = lds_load(entry_addr<1>(st[b][(c + 1) & 3], L.b) + kOddTable);    // te_3
-            l[b][c][2] = lds_load(entry_addr<2>(st[b][(c + 2) & 3], L.a));                // te_0
-            l[b][c][3] = lds_load(entry_addr<3>(st[b][(c + 3) & 3], L.a) + kOddTable);    // te_1
-        }
-    }
-#pragma unroll
-    for (int b = 0; b < NB; b++) {
-#pragma unroll
-        for (int c = 0; c < 4; c++) {
-            uint32_t lo = __builtin_amdgcn_perm(l[b][c][1], l[b][c][0], 0x0c0c0500u);   // l0.b0, l1.b1, 0, 0
-            uint32_t hi = __builtin_amdgcn_perm(l[b][c][3], l[b][c][2], 0x07020c0cu);   // 0, 0, l2.b2, l3.b3
-            out[b][c] = add_round_key_b<M0, M1, M2>(b, bitop3<kOrXor>(lo, hi, seed[c]), 0u, 40 + c, pick);
+            for (int cc = 0; cc < 4; cc++) {
+                const int c = 3 - cc;
+                if (r < 10) {
+                    st[b][c] = add_round_key(keys[b], bitop3<kXor3>(lk[4 * c], lk[4 * c + 1], lk[4 * c + 2]),
+                                             lk[4 * c + 3], 4 * r + c, pick[b]);
+                } else {
+                    // last round: SubBytes + ShiftRows only, S(v) = byte r of the row-r lookup
+                    uint32_t lo = __builtin_amdgcn_perm(lk[4 * c + 1], lk[4 * c + 0], 0x0c0c0500u);   // l0.b0, l1.b1, 0, 0
+                    uint32_t hi = __builtin_amdgcn_perm(lk[4 * c + 3], lk[4 * c + 2], 0x07020c0cu);   // 0, 0, l2.b2, l3.b3
+                    out[b][c] = add_round_key(keys[b], bitop3<kOrXor>(lo, hi, seed[b][c]), 0u, 40 + c, pick[b]);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 }
@@ -240,11 +235,18 @@ __global__ __launch_bounds__(kThreads) void eval_kernel(EvalArgs a)
         const uint32_t x = a.x[e] & mask;
         uint32_t acc = 0;
 
+        // correction words are fetched one level ahead of their use
+        uint4 scw_next = scw_p[e];
+        uint32_t sig_next = 0, leaf_next = 0;
+        if constexpr (CMP) { sig_next = sig_p[e]; leaf_next = leaf_p[e]; }
         for (int i = 0; i < n; i++) {                   // level i + 1
-            const size_t pe = (size_t)i * k.bp + e;
-            const uint4 scw = scw_p[pe];
-            uint32_t sigcw = 0, leaf = 0;
-            if constexpr (CMP) { sigcw = sig_p[pe]; leaf = leaf_p[pe]; }
+            const uint4 scw = scw_next;
+            const uint32_t sigcw = sig_next, leaf = leaf_next;
+            if (i + 1 < n) {
+                const size_t pe = (size_t)(i + 1) * k.bp + e;
+                scw_next = scw_p[pe];
+                if constexpr (CMP) { sig_next = sig_p[pe]; leaf_next = leaf_p[pe]; }
+            }
             const uint32_t b = (x >> (n - 1 - i)) & 1u;  // x[i], most significant first
             const bool right = b != 0;
             const uint32_t pick = 0u - b;                // all ones iff x[i] = 1
@@ -253,7 +255,9 @@ __global__ __launch_bounds__(kThreads) void eval_kernel(EvalArgs a)
             uint32_t child[4];
             if constexpr (CMP) {
                 uint32_t g[2][4];
-                aes_mmo<-1, 2, 2, 2>(g, s, pick, L);    // G_{1+x[i]}(s) and G_3(s)
+                const uint32_t in[2][4] = { { s[0], s[1], s[2], s[3] }, { s[0], s[1], s[2], s[3] } };
+                const uint32_t pk[2] = { pick, 0u };
+                aes_mmo<-1, 2>(g, in, pk, L);            // G_{1+x[i]}(s) and G_3(s)
                 const uint32_t sigma = ((right ? g[1][1] : g[1][0]) ^ (sigcw & tm)) & mask;
                 const uint32_t tau = ((g[1][2] >> b) ^ (t & ((right ? taucw[1] : taucw[0]) >> i))) & 1u;
                 acc += (tau ? leaf : 0u) + sigma;        // out_i, sign applied at the end
@@ -261,7 +265,9 @@ __global__ __launch_bounds__(kThreads) void eval_kernel(EvalArgs a)
                 for (int c = 0; c < 4; c++) child[c] = g[0][c];
             } else {
                 uint32_t g[1][4];
-                aes_mmo<-1, 2, 2, 1>(g, s, pick, L);
+                const uint32_t in[1][4] = { { s[0], s[1], s[2], s[3] } };
+                const uint32_t pk[1] = { pick };
+                aes_mmo<-1>(g, in, pk, L);
 #pragma unroll
                 for (int c = 0; c < 4; c++) child[c] = g[0][c];
             }
@@ -333,16 +339,28 @@ __global__ __launch_bounds__(kThreads) void gen_kernel(GenArgs a)
             const uint32_t abit = (alpha >> (n - 1 - i)) & 1u;   // alpha[i]; Keep = abit, Lose = 1 - abit
             uint32_t g[2][3][4];                          // [party][G_1, G_2, G_3][word]
             if constexpr (CMP) {
-                aes_mmo<0, 1, 2, 3>(g[0], s[0], 0u, L);
-                aes_mmo<0, 1, 2, 3>(g[1], s[1], 0u, L);
+                uint32_t h[6][4];
+                const uint32_t in[6][4] = { { s[0][0], s[0][1], s[0][2], s[0][3] }, { s[0][0], s[0][1], s[0][2], s[0][3] },
+                                            { s[0][0], s[0][1], s[0][2], s[0][3] }, { s[1][0], s[1][1], s[1][2], s[1][3] },
+                                            { s[1][0], s[1][1], s[1][2], s[1][3] }, { s[1][0], s[1][1], s[1][2], s[1][3] } };
+                const uint32_t pk[6] = { 0, 0, 0, 0, 0, 0 };
+                aes_mmo<0, 1, 2, 0, 1, 2>(h, in, pk, L);
+#pragma unroll
+                for (int j = 0; j < 2; j++)
+#pragma unroll
+                    for (int m = 0; m < 3; m++)
+#pragma unroll
+                        for (int c = 0; c < 4; c++) g[j][m][c] = h[3 * j + m][c];
             } else {
-                uint32_t h[2][4];
-                aes_mmo<0, 1, 2, 2>(h, s[0], 0u, L);
+                uint32_t h[4][4];
+                const uint32_t in[4][4] = { { s[0][0], s[0][1], s[0][2], s[0][3] }, { s[0][0], s[0][1], s[0][2], s[0][3] },
+                                            { s[1][0], s[1][1], s[1][2], s[1][3] }, { s[1][0], s[1][1], s[1][2], s[1][3] } };
+                const uint32_t pk[4] = { 0, 0, 0, 0 };
+                aes_mmo<0, 1, 0, 1>(h, in, pk, L);
 #pragma unroll
-                for (int c = 0; c < 4; c++) { g[0][0][c] = h[0][c]; g[0][1][c] = h[1][c]; g[0][2][c] = 0; }
-                aes_mmo<0, 1, 2, 2>(h, s[1], 0u, L);
+                for (int j = 0; j < 2; j++)
 #pragma unroll
-                for (int c = 0; c < 4; c++) { g[1][0][c] = h[0][c]; g[1][1][c] = h[1][c]; g[1][2][c] = 0; }
+                    for (int c = 0; c < 4; c++) { g[j][0][c] = h[2 * j][c]; g[j][1][c] = h[2 * j + 1][c]; g[j][2][c] = 0; }
             }
             // control bits of the children, and the children with that bit cleared
             uint32_t tL[2], tR[2];
