@@ -475,11 +475,25 @@ static bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintp
 
 static bool bad_n(int n) { return n < 1 || n > 32; }
 
-static unsigned grid_for(size_t elems, const DeviceInfo &d)
+struct LaunchShape {
+    unsigned grid, threads;
+};
+
+// One workgroup per CU (its tables take 128 KiB of the CU's LDS).  Large batches: 1024 threads
+// per workgroup and a grid-stride loop.  Batches that would leave CUs idle at that size are
+// spread over all CUs with fewer wavefronts per workgroup instead.
+static LaunchShape shape_for(size_t elems, const DeviceInfo &d)
 {
-    size_t tiles = (elems + kThreads - 1) / kThreads;
-    size_t cap = (size_t)d.cus;                 // one 128 KiB workgroup per CU
-    return (unsigned)(tiles < cap ? tiles : cap);
+    const size_t cus = (size_t)d.cus;
+    size_t threads = (elems + cus - 1) / cus;                  // elements per CU if spread evenly
+    threads = (threads + 63) / 64 * 64;
+    if (threads < 64) threads = 64;
+    if (threads > (size_t)kThreads) threads = kThreads;
+    size_t tiles = (elems + threads - 1) / threads;
+    LaunchShape s;
+    s.threads = (unsigned)threads;
+    s.grid = (unsigned)(tiles < cus ? tiles : cus);
+    return s;
 }
 
 static int check_launch()
@@ -509,10 +523,10 @@ static int gen_common(bool cmp, int n, size_t batch, const uint32_t *d_alpha, co
     a.seed0 = reinterpret_cast<const uint4 *>(d_seed0); a.seed1 = reinterpret_cast<const uint4 *>(d_seed1);
     a.key0 = static_cast<uint8_t *>(d_key0); a.key1 = static_cast<uint8_t *>(d_key1);
     a.batch = batch; a.n = n;
-    const unsigned grid = grid_for(padded_batch(batch), dev);
+    const LaunchShape ls = shape_for(padded_batch(batch), dev);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (cmp) hipLaunchKernelGGL(gen_kernel<true>, dim3(grid), dim3(kThreads), kLdsBytes, st, a);
-    else hipLaunchKernelGGL(gen_kernel<false>, dim3(grid), dim3(kThreads), kLdsBytes, st, a);
+    if (cmp) hipLaunchKernelGGL(gen_kernel<true>, dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
+    else hipLaunchKernelGGL(gen_kernel<false>, dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
     return check_launch();
 }
 
@@ -529,10 +543,10 @@ static int eval_common(bool cmp, int party, int n, size_t batch, const void *d_k
     EvalArgs a;
     a.key = static_cast<const uint8_t *>(d_key); a.x = d_x; a.out = d_out;
     a.batch = batch; a.n = n; a.party = party;
-    const unsigned grid = grid_for(batch, dev);
+    const LaunchShape ls = shape_for(batch, dev);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (cmp) hipLaunchKernelGGL(eval_kernel<true>, dim3(grid), dim3(kThreads), kLdsBytes, st, a);
-    else hipLaunchKernelGGL(eval_kernel<false>, dim3(grid), dim3(kThreads), kLdsBytes, st, a);
+    if (cmp) hipLaunchKernelGGL(eval_kernel<true>, dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
+    else hipLaunchKernelGGL(eval_kernel<false>, dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
     return check_launch();
 }
 
