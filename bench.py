@@ -7,7 +7,8 @@ elements, then both parties' Eval.  The workload is the large-batch configuratio
 HBM before the timed region.  Prints ONE JSON line.
 
   value      comparison evaluations per second per party = B / mean duration of one Eval launch
-  roofline   the dominant kernel (comparison Eval) against the 32-bit integer/bitwise VALU peak
+  roofline   the dominant kernel (comparison Eval) against the LDS read peak that binds it,
+             with the vector-ALU and HBM fractions beside it
   cpu_baseline  the plain-C oracle timed on this host's cores on a bounded sample
 """
 import argparse
@@ -20,15 +21,21 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# ---- work model of the comparison Eval kernel ("Rooflines") -------------
+# ---- work model of the comparison Eval kernel ---------------------
 N_BITS = 32
 AES_BLOCKS_PER_EVAL = 2 * N_BITS            # one child block + one sigma/tau block per level
-VALU_OPS_PER_BLOCK = 320                    # static VALU instructions per AES block in the kernel's ISA
+LOOKUPS_PER_BLOCK = 160                     # 16 table lookups x 10 rounds, 4 bytes each
+LDS_BYTES_PER_EVAL = AES_BLOCKS_PER_EVAL * LOOKUPS_PER_BLOCK * 4
+VALU_OPS_PER_BLOCK = 284                    # vector-ALU instructions per AES block (SQ_INSTS_VALU / blocks)
 TREE_OPS_PER_LEVEL = 30                     # correction-word gating, selects, accumulate
 LANE_OPS_PER_EVAL = AES_BLOCKS_PER_EVAL * VALU_OPS_PER_BLOCK + N_BITS * TREE_OPS_PER_LEVEL
-BYTES_PER_EVAL = 804 + 4 + 4                # key planes read by Eval + x + out
+HBM_BYTES_PER_EVAL = 804 + 4 + 4            # key planes read by Eval + x + out
+PEAK_LDS_GBS = 256 * 128 * 2.4              # 256 CUs x 128 B/clk x 2.4 GHz = 78,643 GB/s
 PEAK_LANE_TOPS = 256 * 64 * 2.4e9 / 1e12    # 256 CUs x 64 lanes x 2.4 GHz = 39.3 T 32-bit lane-ops/s
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per Eval launch at B = 2^22 from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by a plain
+# 1 GiB copy in the same run (profiles/cmp_2p22_hbm_counters.txt)
+MEASURED_HBM_BYTES_2P22 = (3_309_750 + 16_384) * 1024
 
 
 def cpu_baseline(sample: int):
@@ -141,7 +148,9 @@ def main():
     gen_mean = sum(gen_ms) / len(gen_ms)
     evals_per_s = B / (eval_ms * 1e-3)
 
-    achieved_tops = B * LANE_OPS_PER_EVAL / (eval_ms * 1e-3) / 1e12
+    lds_gbs = B * LDS_BYTES_PER_EVAL / (eval_ms * 1e-3) / 1e9
+    lane_tops = B * LANE_OPS_PER_EVAL / (eval_ms * 1e-3) / 1e12
+    hbm_gbs = B * HBM_BYTES_PER_EVAL / (eval_ms * 1e-3) / 1e9
     out = {
         "metric": "FSS comparison evals/sec per party (n=32, lambda=128)",
         "value": evals_per_s,
@@ -162,16 +171,21 @@ def main():
         "gen_ms": gen_mean,
         "gen_key_pairs_per_s": B / (gen_mean * 1e-3),
         "step_evals_per_s_incl_gen": 2 * B / (wall / args.steps),
+        # The AES of this path is table-driven out of LDS, and the LDS read port is the unit that
+        # binds: 160 four-byte lookups per AES block against 128 B/clk/CU.
         "roofline": {
-            "bound": "alu",
+            "bound": "lds",
             "kernel": "eval_kernel<cmp>",
-            "achieved": achieved_tops,
-            "peak": PEAK_LANE_TOPS,
-            "unit": "T 32-bit lane-ops/s",
-            "frac": achieved_tops / PEAK_LANE_TOPS,
-            "traffic": None,
-            "lane_ops_per_eval": LANE_OPS_PER_EVAL,
-            "hbm_frac": BYTES_PER_EVAL * evals_per_s / 1e9 / PEAK_HBM_GBS,
+            "achieved": lds_gbs,
+            "peak": PEAK_LDS_GBS,
+            "unit": "GB/s",
+            "frac": lds_gbs / PEAK_LDS_GBS,
+            "traffic": MEASURED_HBM_BYTES_2P22 if B == (1 << 22) else None,
+            "traffic_unit": "HBM bytes per Eval launch (rocprofv3 FETCH_SIZE+WRITE_SIZE, scaled)",
+            "alu": {"achieved": lane_tops, "peak": PEAK_LANE_TOPS, "unit": "T 32-bit lane-ops/s",
+                    "frac": lane_tops / PEAK_LANE_TOPS, "lane_ops_per_eval": LANE_OPS_PER_EVAL},
+            "hbm": {"achieved": hbm_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": hbm_gbs / PEAK_HBM_GBS,
+                    "bytes_per_eval": HBM_BYTES_PER_EVAL},
         },
     }
     if args.cpu_sample > 0:

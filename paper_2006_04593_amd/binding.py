@@ -41,6 +41,15 @@ def build(verbose: bool = False) -> str:
         print(res.stderr)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed building libfss_mi355.so")
+    # the stand-alone micro-benchmark that backs the choice of AES engine
+    bench = [hipcc] + [f for f in HIPCC_FLAGS if f not in ("-shared", "-fPIC")] + \
+        [os.path.join(_CSRC, "aes_engine_bench.hip"), "-o", os.path.join(_HERE, "aes_engine_bench")]
+    res = subprocess.run(bench, capture_output=True, text=True)
+    if verbose or res.returncode != 0:
+        print(res.stdout)
+        print(res.stderr)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed building aes_engine_bench")
     global _lib
     _lib = None
     return _SO

@@ -1,0 +1,213 @@
+// Stand-alone micro-benchmark behind the choice of AES engine (one MI355X, no inputs):
+//   1. raw Matyas-Meyer-Oseas blocks/s of the LDS-table engine (aes_lds.h), as the kernels use it;
+//   2. the same for the ALU-only bit-plane engine (aes_bitplane.h);
+//   3. the machine rates that bound them: conflict-free ds_read_b32 lookups per clock per CU
+//      (the kernel's 32-copy access pattern and an unreplicated table for comparison), and the
+//      issue rate of the vector-ALU instructions both engines are made of.
+// All figures come from HIP events around long launches that fill every CU.
+//
+// usage: aes_engine_bench            (prints a table; exit status 0)
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "aes_bitplane.h"
+#include "aes_lds.h"
+
+#define CK(x)                                                                        \
+    do {                                                                             \
+        hipError_t e_ = (x);                                                         \
+        if (e_ != hipSuccess) {                                                      \
+            printf("HIP error %s at line %d\n", hipGetErrorString(e_), __LINE__);   \
+            return 1;                                                                \
+        }                                                                            \
+    } while (0)
+
+using namespace fss;
+
+// ---- engine 1: LDS tables, two chained blocks per lane per iteration (keys 1/2 per lane + key 3)
+__global__ __launch_bounds__(kThreads) void lds_engine(uint32_t *out, int iters)
+{
+    extern __shared__ uint32_t lds[];
+    fill_tables(lds);
+    __syncthreads();
+    const LaneBase L = lane_base(lds);
+    uint32_t s[4] = { threadIdx.x * 2654435761u, blockIdx.x * 40503u + 1u, threadIdx.x ^ 0x5bd1e995u, 7u };
+    for (int it = 0; it < iters; it++) {
+        uint32_t g[2][4];
+        const uint32_t in[2][4] = { { s[0], s[1], s[2], s[3] }, { s[0], s[1], s[2], s[3] } };
+        const uint32_t pk[2] = { 0u - (s[3] & 1u), 0u };
+        aes_mmo<-1, 2>(g, in, pk, L);
+#pragma unroll
+        for (int c = 0; c < 4; c++) s[c] = g[0][c] ^ g[1][(c + 1) & 3];
+    }
+    out[blockIdx.x * blockDim.x + threadIdx.x] = s[0] ^ s[1] ^ s[2] ^ s[3];
+}
+
+// ---- engine 2: bit planes, eight chained blocks per lane per iteration
+__global__ __launch_bounds__(kThreads) void bitplane_engine(uint32_t *out, int iters)
+{
+    bp::W a[8][4];
+    for (int j = 0; j < 8; j++)
+        for (int c = 0; c < 4; c++) a[j][c] = threadIdx.x * 2654435761u + blockIdx.x * 40503u + j * 97u + c;
+    const bp::W pick = ((threadIdx.x * 0x9e3779b9u) >> 24) * 0x01010101u;
+    for (int it = 0; it < iters; it++) {
+        bp::W o[8][4];
+        bp::mmo8<bp::kPickLowK3High>(o, a, pick);
+        for (int j = 0; j < 8; j++)
+            for (int c = 0; c < 4; c++) a[j][c] = o[j][c];
+    }
+    uint32_t acc = 0;
+    for (int j = 0; j < 8; j++)
+        for (int c = 0; c < 4; c++) acc ^= a[j][c];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = acc;
+}
+
+// ---- machine rate: ds_read_b32 with per-lane addresses and (almost) no ALU work beside it
+// REPL = true: the kernels' pattern ((entry << 8) | copy of lane); false: one 1-KiB table for all lanes.
+// The 16 addresses of a lane are drawn once; every iteration issues the 16 loads, waits, and
+// folds the results with 16 two-operand XORs.
+template <bool REPL>
+__global__ __launch_bounds__(kThreads) void lds_rate(uint32_t *out, int iters)
+{
+    extern __shared__ uint32_t lds[];
+    for (uint32_t j = threadIdx.x; j < kLdsBytes / 4; j += blockDim.x) lds[j] = j * 2654435761u;
+    __syncthreads();
+    const uint32_t lane4 = (threadIdx.x & 31u) << 2;
+    uint32_t r = threadIdx.x * 747796405u + blockIdx.x * 2891336453u + 12345u, acc = 0;
+    uint32_t a[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) {
+        r = r * 1664525u + 1013904223u;
+        const uint32_t e = (r >> 13) & 255u;
+        a[k] = REPL ? ((e << 8) | lane4 | ((k & 1) << 7) | ((k & 2) << 15)) : ((e << 2) | (k << 10));
+    }
+    for (int it = 0; it < iters; it++) {
+        uint32_t v[16];
+#pragma unroll
+        for (int k = 0; k < 16; k++) asm volatile("ds_read_b32 %0, %1" : "=v"(v[k]) : "v"(a[k]) : "memory");
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]), "+v"(v[6]), "+v"(v[7]),
+                       "+v"(v[8]), "+v"(v[9]), "+v"(v[10]), "+v"(v[11]), "+v"(v[12]), "+v"(v[13]), "+v"(v[14]), "+v"(v[15])
+                     :
+                     : "memory");
+#pragma unroll
+        for (int k = 0; k < 16; k++) acc ^= v[k];
+    }
+    out[blockIdx.x * blockDim.x + threadIdx.x] = acc;
+}
+
+// ---- machine rate: vector-ALU instructions, 8 independent chains per wavefront
+#define FSS_ALU_LOOP(INSTRS)                                                                                  \
+    asm volatile("v_mov_b32 v10, %1\n v_mov_b32 v11, %1\n v_mov_b32 v12, %1\n v_mov_b32 v13, %1\n"            \
+                 "v_mov_b32 v14, %1\n v_mov_b32 v15, %1\n v_mov_b32 v16, %1\n v_mov_b32 v17, %1\n"            \
+                 "v_mov_b32 v18, %1\n v_mov_b32 v19, %1\n v_mov_b32 v20, %1\n v_mov_b32 v21, %1\n"            \
+                 "s_mov_b32 s20, %2\n s_mov_b32 s21, 0x03020500\n"                                            \
+                 "1:\n .rept 16\n" INSTRS ".endr\n"                                                           \
+                 "s_sub_u32 s20, s20, 1\n s_cmp_lg_u32 s20, 0\n s_cbranch_scc1 1b\n"                          \
+                 "v_xor_b32 %0, v10, v11\n v_xor_b32 %0, %0, v12\n v_xor_b32 %0, %0, v13\n"                   \
+                 "v_xor_b32 %0, %0, v14\n v_xor_b32 %0, %0, v15\n v_xor_b32 %0, %0, v16\n v_xor_b32 %0, %0, v17\n" \
+                 : "=&v"(r)                                                                                   \
+                 : "v"(seed), "s"(iters)                                                                      \
+                 : "v10", "v11", "v12", "v13", "v14", "v15", "v16", "v17", "v18", "v19", "v20", "v21", "s20", "s21", "scc", "memory")
+#define FSS_ALU_8(op, b, c)                                                                       \
+    op " v10, v10, " b "18, " c "\n" op " v11, v11, " b "19, " c "\n" op " v12, v12, " b "20, " c "\n" \
+    op " v13, v13, " b "21, " c "\n" op " v14, v14, " b "18, " c "\n" op " v15, v15, " b "19, " c "\n" \
+    op " v16, v16, " b "20, " c "\n" op " v17, v17, " b "21, " c "\n"
+
+template <int OP>
+__global__ __launch_bounds__(kThreads) void alu_rate(uint32_t *out, int iters)
+{
+    uint32_t seed = threadIdx.x + blockIdx.x, r;
+    if (OP == 0) FSS_ALU_LOOP(FSS_ALU_8("v_perm_b32", "v", "s21"));
+    if (OP == 1) FSS_ALU_LOOP(FSS_ALU_8("v_bitop3_b32", "v", "v19 bitop3:0x96"));
+    if (OP == 2) FSS_ALU_LOOP(FSS_ALU_8("v_bitop3_b32", "v", "s21 bitop3:0x96"));
+    if (OP == 3) FSS_ALU_LOOP("v_xor_b32 v10, v10, v18\n v_xor_b32 v11, v11, v19\n v_xor_b32 v12, v12, v20\n v_xor_b32 v13, v13, v21\n"
+                              "v_xor_b32 v14, v14, v18\n v_xor_b32 v15, v15, v19\n v_xor_b32 v16, v16, v20\n v_xor_b32 v17, v17, v21\n");
+    if (OP == 4) FSS_ALU_LOOP(FSS_ALU_8("v_alignbit_b32", "v", "8"));
+    out[blockIdx.x * blockDim.x + threadIdx.x] = r;
+}
+
+template <typename F>
+static int time_launch(F launch, float *best_ms)
+{
+    hipEvent_t a, b;
+    CK(hipEventCreate(&a));
+    CK(hipEventCreate(&b));
+    *best_ms = 1e30f;
+    for (int rep = 0; rep < 3; rep++) {
+        CK(hipEventRecord(a, 0));
+        launch();
+        CK(hipEventRecord(b, 0));
+        CK(hipEventSynchronize(b));
+        CK(hipGetLastError());
+        float ms;
+        CK(hipEventElapsedTime(&ms, a, b));
+        if (ms < *best_ms) *best_ms = ms;
+    }
+    return 0;
+}
+
+int main()
+{
+    hipDeviceProp_t p;
+    CK(hipGetDeviceProperties(&p, 0));
+    const int cus = p.multiProcessorCount;
+    printf("device %s, %d CUs, nominal clock %.0f MHz, LDS per workgroup %zu B\n", p.gcnArchName, cus, p.clockRate / 1e3,
+           (size_t)p.sharedMemPerBlock);
+    uint32_t *out;
+    CK(hipMalloc(&out, (size_t)cus * 8 * kThreads * 4));
+    CK(hipFuncSetAttribute((const void *)lds_engine, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes));
+    CK(hipFuncSetAttribute((const void *)lds_rate<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes));
+    CK(hipFuncSetAttribute((const void *)lds_rate<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes));
+    float ms;
+    const double ghz = 2.4;
+
+    printf("\nAES engines (Matyas-Meyer-Oseas blocks, every CU busy)\n");
+    {
+        const int iters = 2000;
+        if (time_launch([&] { hipLaunchKernelGGL(lds_engine, dim3(cus), dim3(kThreads), kLdsBytes, 0, out, iters); }, &ms)) return 1;
+        const double blocks = (double)cus * kThreads * iters * 2;
+        printf("  LDS-table engine   %8.3f ms  %7.1f G blocks/s  %5.2f clk/block/CU at %.1f GHz\n", ms, blocks / ms / 1e6,
+               ms * 1e-3 * ghz * 1e9 * cus / blocks, ghz);
+    }
+    {
+        const int iters = 250;
+        if (time_launch([&] { hipLaunchKernelGGL(bitplane_engine, dim3(cus), dim3(kThreads), 0, 0, out, iters); }, &ms)) return 1;
+        const double blocks = (double)cus * kThreads * iters * 8;
+        printf("  bit-plane engine   %8.3f ms  %7.1f G blocks/s  %5.2f clk/block/CU at %.1f GHz\n", ms, blocks / ms / 1e6,
+               ms * 1e-3 * ghz * 1e9 * cus / blocks, ghz);
+    }
+
+    printf("\nds_read_b32 with data-dependent addresses, 16 wavefronts per CU\n");
+    {
+        const int iters = 20000;
+        const double lanes = (double)cus * kThreads * iters * 16;
+        if (time_launch([&] { hipLaunchKernelGGL(lds_rate<true>, dim3(cus), dim3(kThreads), kLdsBytes, 0, out, iters); }, &ms)) return 1;
+        printf("  32 copies per entry (kernels' layout) %8.3f ms  %6.1f lookups/clk/CU  %6.1f TB/s\n", ms,
+               lanes / (ms * 1e-3) / cus / (ghz * 1e9), lanes * 4 / (ms * 1e-3) / 1e12);
+        if (time_launch([&] { hipLaunchKernelGGL(lds_rate<false>, dim3(cus), dim3(kThreads), kLdsBytes, 0, out, iters); }, &ms)) return 1;
+        printf("  one 1-KiB table, no replication       %8.3f ms  %6.1f lookups/clk/CU  %6.1f TB/s\n", ms,
+               lanes / (ms * 1e-3) / cus / (ghz * 1e9), lanes * 4 / (ms * 1e-3) / 1e12);
+    }
+
+    printf("\nvector-ALU issue rate, 4 wavefronts per SIMD, 8 independent chains\n");
+    {
+        const int iters = 20000;
+        const double laneops = (double)cus * kThreads * iters * 128;
+        const char *names[5] = { "v_perm_b32 (v,v,s)", "v_bitop3_b32 (v,v,v)", "v_bitop3_b32 (v,v,s)", "v_xor_b32 (v,v)", "v_alignbit_b32 (v,v,imm)" };
+        for (int op = 0; op < 5; op++) {
+            int rc = 0;
+            if (op == 0) rc = time_launch([&] { hipLaunchKernelGGL(alu_rate<0>, dim3(cus), dim3(kThreads), 0, 0, out, iters); }, &ms);
+            if (op == 1) rc = time_launch([&] { hipLaunchKernelGGL(alu_rate<1>, dim3(cus), dim3(kThreads), 0, 0, out, iters); }, &ms);
+            if (op == 2) rc = time_launch([&] { hipLaunchKernelGGL(alu_rate<2>, dim3(cus), dim3(kThreads), 0, 0, out, iters); }, &ms);
+            if (op == 3) rc = time_launch([&] { hipLaunchKernelGGL(alu_rate<3>, dim3(cus), dim3(kThreads), 0, 0, out, iters); }, &ms);
+            if (op == 4) rc = time_launch([&] { hipLaunchKernelGGL(alu_rate<4>, dim3(cus), dim3(kThreads), 0, 0, out, iters); }, &ms);
+            if (rc) return 1;
+            printf("  %-26s %8.3f ms  %6.1f T lane-ops/s  %6.1f lanes/clk/CU at %.1f GHz\n", names[op], ms, laneops / (ms * 1e-3) / 1e12,
+                   laneops / (ms * 1e-3) / cus / (ghz * 1e9), ghz);
+        }
+    }
+    CK(hipFree(out));
+    return 0;
+}
