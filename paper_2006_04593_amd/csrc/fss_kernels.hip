@@ -179,18 +179,18 @@ __global__ __launch_bounds__(kThreads) void gen_kernel(GenArgs a)
             const uint32_t abit = (alpha >> (n - 1 - i)) & 1u;   // alpha[i]; Keep = abit, Lose = 1 - abit
             uint32_t g[2][3][4];                          // [party][G_1, G_2, G_3][word]
             if constexpr (CMP) {
-                uint32_t h[6][4];
-                const uint32_t in[6][4] = { { s[0][0], s[0][1], s[0][2], s[0][3] }, { s[0][0], s[0][1], s[0][2], s[0][3] },
-                                            { s[0][0], s[0][1], s[0][2], s[0][3] }, { s[1][0], s[1][1], s[1][2], s[1][3] },
-                                            { s[1][0], s[1][1], s[1][2], s[1][3] }, { s[1][0], s[1][1], s[1][2], s[1][3] } };
-                const uint32_t pk[6] = { 0, 0, 0, 0, 0, 0 };
-                aes_mmo<0, 1, 2, 0, 1, 2>(h, in, pk, L);
 #pragma unroll
-                for (int j = 0; j < 2; j++)
+                for (int j = 0; j < 2; j++) {
+                    uint32_t h[3][4];
+                    const uint32_t in[3][4] = { { s[j][0], s[j][1], s[j][2], s[j][3] }, { s[j][0], s[j][1], s[j][2], s[j][3] },
+                                                { s[j][0], s[j][1], s[j][2], s[j][3] } };
+                    const uint32_t pk[3] = { 0, 0, 0 };
+                    aes_mmo<0, 1, 2>(h, in, pk, L);
 #pragma unroll
                     for (int m = 0; m < 3; m++)
 #pragma unroll
-                        for (int c = 0; c < 4; c++) g[j][m][c] = h[3 * j + m][c];
+                        for (int c = 0; c < 4; c++) g[j][m][c] = h[m][c];
+                }
             } else {
                 uint32_t h[4][4];
                 const uint32_t in[4][4] = { { s[0][0], s[0][1], s[0][2], s[0][3] }, { s[0][0], s[0][1], s[0][2], s[0][3] },

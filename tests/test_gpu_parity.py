@@ -246,3 +246,12 @@ def test_config4_maxpool_dependent_rounds():
 def test_config5_large_batch_sampled():
     w = W.config_workload(5)
     check_sampled("cmp", 32, w.gen, w.x, samples=8192, seed=5)
+
+
+def test_key_buffer_beyond_4_gib():
+    """B = 2^23 + 1000: one party's key is 6.8 GB, so every plane offset past the first few
+    needs 64-bit arithmetic; sampled elements (including the first and the last) against the oracle."""
+    n, batch = 32, (1 << 23) + 1000
+    w = W.uniform_workload("cmp", n, batch, seed=823)
+    assert fss.cmp_key_bytes(n, batch) > (1 << 32)
+    check_sampled("cmp", n, w.gen, w.x, samples=2048, seed=23)
