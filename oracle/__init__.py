@@ -63,6 +63,14 @@ def load(path: str) -> C.CDLL:
     L.oracle_eval_trace.argtypes = [C.c_int, C.c_int, C.c_int, C.c_size_t, vp, C.c_size_t, C.c_uint32,
                                     u8p, i32p, u32p, i32p, u32p, u32p]
     L.oracle_eval_trace.restype = C.c_int
+    L.oracle_sign_mask.argtypes = [C.c_int, C.c_size_t, vp, u32p, u32p]
+    L.oracle_sign_mask.restype = C.c_int
+    L.oracle_sign_eval.argtypes = [C.c_int, C.c_int, C.c_size_t, vp, u32p, u32p, u32p]
+    L.oracle_sign_eval.restype = C.c_int
+    L.oracle_relu_open.argtypes = [C.c_int, C.c_int, C.c_size_t, vp, u32p, u32p, u32p, u32p, u32p, u32p, u32p]
+    L.oracle_relu_open.restype = C.c_int
+    L.oracle_relu_finish.argtypes = [C.c_int, C.c_int, C.c_size_t, u32p, u32p, u32p, u32p, u32p, u32p, u32p, u32p]
+    L.oracle_relu_finish.restype = C.c_int
     L.oracle_set_threads.argtypes = [C.c_int]
     L.oracle_set_threads.restype = C.c_int
     L.oracle_init()
@@ -171,6 +179,46 @@ def eval_trace(kind: str, party: int, n: int, batch: int, key: np.ndarray, e: in
     if rc != 0:
         raise ValueError(f"oracle trace failed: {rc}")
     return {"s": s, "t": t, "sigma": sigma, "tau": tau, "out": outs, "share": int(share.value)}
+
+
+def sign_mask(n: int, key: np.ndarray, y_share) -> np.ndarray:
+    y_share = _u32(y_share)
+    out = np.zeros(y_share.shape[0], dtype=np.uint32)
+    rc = lib().oracle_sign_mask(n, y_share.shape[0], key.ctypes.data, _p(y_share, C.c_uint32), _p(out, C.c_uint32))
+    if rc != 0:
+        raise ValueError(f"oracle sign_mask failed: {rc}")
+    return out
+
+
+def sign_eval(party: int, n: int, key: np.ndarray, masked0, masked1) -> np.ndarray:
+    m0, m1 = _u32(masked0), _u32(masked1)
+    out = np.zeros(m0.shape[0], dtype=np.uint32)
+    rc = lib().oracle_sign_eval(party, n, m0.shape[0], key.ctypes.data, _p(m0, C.c_uint32), _p(m1, C.c_uint32), _p(out, C.c_uint32))
+    if rc != 0:
+        raise ValueError(f"oracle sign_eval failed: {rc}")
+    return out
+
+
+def relu_open(party: int, n: int, key: np.ndarray, masked0, masked1, y_share, tri_a, tri_b):
+    arrs = [_u32(a) for a in (masked0, masked1, y_share, tri_a, tri_b)]
+    batch = arrs[0].shape[0]
+    delta = np.zeros(batch, dtype=np.uint32)
+    eps = np.zeros(batch, dtype=np.uint32)
+    rc = lib().oracle_relu_open(party, n, batch, key.ctypes.data, *[_p(a, C.c_uint32) for a in arrs],
+                                _p(delta, C.c_uint32), _p(eps, C.c_uint32))
+    if rc != 0:
+        raise ValueError(f"oracle relu_open failed: {rc}")
+    return delta, eps
+
+
+def relu_finish(party: int, n: int, delta0, delta1, eps0, eps1, tri_a, tri_b, tri_c) -> np.ndarray:
+    arrs = [_u32(a) for a in (delta0, delta1, eps0, eps1, tri_a, tri_b, tri_c)]
+    batch = arrs[0].shape[0]
+    out = np.zeros(batch, dtype=np.uint32)
+    rc = lib().oracle_relu_finish(party, n, batch, *[_p(a, C.c_uint32) for a in arrs], _p(out, C.c_uint32))
+    if rc != 0:
+        raise ValueError(f"oracle relu_finish failed: {rc}")
+    return out
 
 
 def set_threads(threads: int) -> int:

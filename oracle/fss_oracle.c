@@ -20,6 +20,9 @@
  * AES-128 itself follows FIPS-197 byte by byte (S-box built from the field inverse and the
  * affine map, no lookup tables typed in, no intrinsics).
  *
+ * Also here, around the comparison: the Sign protocol (Algorithm 5) and ReLU as comparison
+ * plus one pointwise product with a multiplication triple (section 4.2).
+ *
  * Pins (tests/test_oracle_*.py): FIPS-197 known answers and the OpenSSL command-line tool
  * for AES; the correctness definition Eval_0 + Eval_1 = f(x) mod 2^n for EVERY x at n = 8
  * and n = 12 and for sampled / edge x at n = 32; the per-level facts of the correctness
@@ -566,6 +569,98 @@ int oracle_eval_trace(int cmp, int party, int n, size_t batch, const void *key, 
     memset(tau, 0, sizeof(int32_t) * (size_t)(n + 1));
     memset(outs, 0, sizeof(uint32_t) * (size_t)(n + 2));
     *share = eval_one(cmp, party, n, &k, e, x, &tr);
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* Sign protocol (Algorithm 5) and ReLU (section 4.2) around the comparison Eval          */
+/* ------------------------------------------------------------------------------------ */
+
+/* Algorithm 5, "publish [[alpha]]_j + [[y]]_j": the masked share party j sends out.
+ * [[alpha]]_j is the first plane of the key. */
+int oracle_sign_mask(int n, size_t batch, const void *key, const uint32_t *y_share, uint32_t *masked)
+{
+    if (bad_n(n)) return ORACLE_EINVAL;
+    if (batch == 0) return ORACLE_OK;
+    if (!key || !y_share || !masked) return ORACLE_EINVAL;
+    key_view_t k;
+    view_cmp(&k, (void *)key, n, batch);
+    const uint32_t mask = ring_mask(n);
+    for (size_t e = 0; e < batch; e++)
+        masked[e] = (y_share[e] + le32(k.alpha_share + 4 * e)) & mask;
+    return ORACLE_OK;
+}
+
+/* Algorithm 5, the rest: x = alpha + y is revealed as the sum of the two published values,
+ * then [[T]]_j = Eval(j, k_j, x). */
+int oracle_sign_eval(int party, int n, size_t batch, const void *key, const uint32_t *masked0,
+                     const uint32_t *masked1, uint32_t *out)
+{
+    if (bad_n(n) || (party != 0 && party != 1)) return ORACLE_EINVAL;
+    if (batch == 0) return ORACLE_OK;
+    if (!key || !masked0 || !masked1 || !out) return ORACLE_EINVAL;
+    oracle_init();
+    key_view_t k;
+    view_cmp(&k, (void *)key, n, batch);
+    const uint32_t mask = ring_mask(n);
+    long long b = (long long)batch;
+#pragma omp parallel for schedule(static)
+    for (long long e = 0; e < b; e++) {
+        uint32_t x = (masked0[e] + masked1[e]) & mask;
+        out[e] = eval_one(1, party, n, &k, (size_t)e, x, NULL);
+    }
+    return ORACLE_OK;
+}
+
+/* ReLU(y) = y . 1{y > 0} = y . (1 - 1{y <= 0}): the comparison, then one pointwise product of
+ * shared values with a multiplication triple ([[a]], [[b]], [[c = a.b]]) as in the MatMul
+ * paragraph of section 4.2: reveal (delta, eps) = (u - a, v - b), then
+ * [[u.v]] = delta.[[b]] + eps.[[a]] + delta.eps + [[c]] (the public term added by one party).
+ * Here u = y and v = 1 - 1{y <= 0}.
+ *
+ * relu_open: party j's second-round messages.
+ *   w_j     = Eval(j, k_j, x)                       share of 1{y <= 0} (up to the Sign failure)
+ *   v_j     = [j = 0] - w_j                          share of 1{y > 0}
+ *   delta_j = [[y]]_j - [[a]]_j,  eps_j = v_j - [[b]]_j                                     */
+int oracle_relu_open(int party, int n, size_t batch, const void *key, const uint32_t *masked0,
+                     const uint32_t *masked1, const uint32_t *y_share, const uint32_t *tri_a,
+                     const uint32_t *tri_b, uint32_t *delta, uint32_t *eps)
+{
+    if (bad_n(n) || (party != 0 && party != 1)) return ORACLE_EINVAL;
+    if (batch == 0) return ORACLE_OK;
+    if (!key || !masked0 || !masked1 || !y_share || !tri_a || !tri_b || !delta || !eps) return ORACLE_EINVAL;
+    oracle_init();
+    key_view_t k;
+    view_cmp(&k, (void *)key, n, batch);
+    const uint32_t mask = ring_mask(n);
+    long long b = (long long)batch;
+#pragma omp parallel for schedule(static)
+    for (long long e = 0; e < b; e++) {
+        uint32_t x = (masked0[e] + masked1[e]) & mask;
+        uint32_t w = eval_one(1, party, n, &k, (size_t)e, x, NULL);
+        uint32_t v = ((party == 0 ? 1u : 0u) - w) & mask;
+        delta[e] = (y_share[e] - tri_a[e]) & mask;
+        eps[e] = (v - tri_b[e]) & mask;
+    }
+    return ORACLE_OK;
+}
+
+/* relu_finish: [[ReLU(y)]]_j from the revealed delta = delta_0 + delta_1, eps = eps_0 + eps_1. */
+int oracle_relu_finish(int party, int n, size_t batch, const uint32_t *delta0, const uint32_t *delta1,
+                       const uint32_t *eps0, const uint32_t *eps1, const uint32_t *tri_a,
+                       const uint32_t *tri_b, const uint32_t *tri_c, uint32_t *out)
+{
+    if (bad_n(n) || (party != 0 && party != 1)) return ORACLE_EINVAL;
+    if (batch == 0) return ORACLE_OK;
+    if (!delta0 || !delta1 || !eps0 || !eps1 || !tri_a || !tri_b || !tri_c || !out) return ORACLE_EINVAL;
+    const uint32_t mask = ring_mask(n);
+    for (size_t e = 0; e < batch; e++) {
+        uint32_t delta = (delta0[e] + delta1[e]) & mask;
+        uint32_t eps = (eps0[e] + eps1[e]) & mask;
+        uint32_t z = delta * tri_b[e] + eps * tri_a[e] + tri_c[e];
+        if (party == 0) z += delta * eps;
+        out[e] = z & mask;
+    }
     return ORACLE_OK;
 }
 

@@ -3,8 +3,9 @@
 This module holds no arithmetic of the method itself (no PRG, no tree walk, no key
 layout): it only draws the random values that key generation and evaluation take as
 *arguments* -- the secret offsets alpha, the alpha-share randomness r, both parties'
-root seeds and the public inputs x -- so that the CPU oracle and the HIP library can be
-fed identical bytes.  Both the tests and the benchmark import it; neither the oracle nor
+root seeds and the public inputs x, and for the ReLU layer the additive shares of the
+activations and the dealer's multiplication triples -- so that the CPU oracle and the HIP
+library can be fed identical bytes.  Both the tests and the benchmark import it; neither the oracle nor
 the HIP path does.
 
 The paper samples alpha and the root seeds uniformly inside KeyGen (initialisation lines
@@ -111,6 +112,34 @@ def relu_workload(batch: int, seed: int, n: int = 32, scale_bits: int = FRAC_BIT
     y = fixed_point_normal(rng, batch, scale_bits)
     x = ((y + g.alpha.astype(np.int64)) & ring_mask(n)).astype(np.uint32)
     return Workload(name="relu", kind="cmp", gen=g, x=x, extra={"y": y})
+
+
+@dataclass
+class ReluInputs:
+    """Per-party inputs of a shared ReLU layer: additive shares of the activations and of one
+    multiplication triple per element (dealer material, like the keys): c = a * b mod 2^n."""
+    y_share: tuple           # ([B] uint32, [B] uint32)
+    tri_a: tuple
+    tri_b: tuple
+    tri_c: tuple
+
+
+def additive_shares(rng: np.random.Generator, n: int, value: np.ndarray):
+    m = np.uint64(ring_mask(n))
+    v = value.astype(np.uint64) & m
+    s0 = uniform_ring(rng, n, v.shape[0]).astype(np.uint64)
+    s1 = (v - s0) & m
+    return s0.astype(np.uint32), s1.astype(np.uint32)
+
+
+def relu_inputs(rng: np.random.Generator, n: int, y: np.ndarray) -> ReluInputs:
+    m = np.uint64(ring_mask(n))
+    batch = y.shape[0]
+    a = uniform_ring(rng, n, batch).astype(np.uint64)
+    b = uniform_ring(rng, n, batch).astype(np.uint64)
+    c = (a * b) & m
+    return ReluInputs(y_share=additive_shares(rng, n, y.astype(np.int64).astype(np.uint64)),
+                      tri_a=additive_shares(rng, n, a), tri_b=additive_shares(rng, n, b), tri_c=additive_shares(rng, n, c))
 
 
 def maxpool_taps(seed: int, channels: int = 64, hw: int = 112) -> np.ndarray:

@@ -41,6 +41,13 @@ MUTANTS = [
      "st[4 * c + 0] = g_mul3[a[0]] ^ g_mul2[a[1]] ^ a[2] ^ a[3];", "aes"),
     ("affine_constant_wrong", "(0x63 >> i)) & 1;", "(0x36 >> i)) & 1;", "aes"),
     ("mmo_feedforward_dropped", "out[i] = enc[i] ^ seed[i];", "out[i] = enc[i];", "prg"),
+    ("relu_public_product_dropped", "if (party == 0) z += delta * eps;", "", "relu"),
+    ("relu_constant_one_dropped", "uint32_t v = ((party == 0 ? 1u : 0u) - w) & mask;", "uint32_t v = (0u - w) & mask;", "relu"),
+    ("relu_eps_sign", "eps[e] = (v - tri_b[e]) & mask;", "eps[e] = (v + tri_b[e]) & mask;", "relu"),
+    ("relu_triple_operands_swapped", "uint32_t z = delta * tri_b[e] + eps * tri_a[e] + tri_c[e];",
+     "uint32_t z = delta * tri_a[e] + eps * tri_b[e] + tri_c[e];", "relu"),
+    ("sign_mask_subtracts", "masked[e] = (y_share[e] + le32(k.alpha_share + 4 * e)) & mask;",
+     "masked[e] = (y_share[e] - le32(k.alpha_share + 4 * e)) & mask;", "relu"),
 ]
 
 
@@ -79,9 +86,29 @@ def prg_definition_holds():
     return oracle.prg(2, s) == bytes(a ^ b for a, b in zip(enc, s))
 
 
+def relu_identity_holds(n=8):
+    """z_0 + z_1 = y (1 - 1{y + alpha <= alpha}) for every y, and the reveal is y + alpha."""
+    size = 1 << n
+    y = np.arange(size, dtype=np.int64)
+    rng = np.random.default_rng(4242)
+    g = W.gen_inputs(rng, n, size)
+    ri = W.relu_inputs(rng, n, y)
+    k = oracle.gen("cmp", n, g.alpha, g.r, g.seed0, g.seed1)
+    masked = [oracle.sign_mask(n, k[j], ri.y_share[j]) for j in (0, 1)]
+    op = [oracle.relu_open(j, n, k[j], masked[0], masked[1], ri.y_share[j], ri.tri_a[j], ri.tri_b[j]) for j in (0, 1)]
+    z = [oracle.relu_finish(j, n, op[0][0], op[1][0], op[0][1], op[1][1], ri.tri_a[j], ri.tri_b[j], ri.tri_c[j]) for j in (0, 1)]
+    mask = W.ring_mask(n)
+    x = (masked[0] + masked[1]) & np.uint32(mask)
+    if not np.array_equal(x, ((y + g.alpha.astype(np.int64)) & mask).astype(np.uint32)):
+        return False
+    le = (x <= g.alpha).astype(np.uint64)
+    return np.array_equal((z[0] + z[1]) & np.uint32(mask), ((y.astype(np.uint64) * (1 - le)) & mask).astype(np.uint32))
+
+
 def test_unmodified_oracle_passes_the_compact_pins():
     assert reconstruction_holds("cmp") and reconstruction_holds("eq")
     assert aes_known_answer_holds() and prg_definition_holds()
+    assert relu_identity_holds()
 
 
 @pytest.mark.parametrize("name,old,new,pin", MUTANTS, ids=[m[0] for m in MUTANTS])
@@ -91,6 +118,8 @@ def test_planted_mistake_is_caught(tmp_path, monkeypatch, name, old, new, pin):
         assert not aes_known_answer_holds()
     elif pin == "prg":
         assert aes_known_answer_holds() and not prg_definition_holds()
+    elif pin == "relu":
+        assert reconstruction_holds("cmp") and not relu_identity_holds()
     elif pin == "cmp":
         assert not reconstruction_holds("cmp")
     else:
