@@ -66,6 +66,74 @@ def cpu_baseline(sample: int):
     }
 
 
+def relu_layer_bench(args, dev):
+    """One shared ReLU layer (paper section 4.2) of 64 x 112 x 112 fixed-point activations, both
+    parties on the one GPU: a step = each party's Sign mask, fused comparison + open round, finish.
+    Keys and multiplication triples are dealer material, generated before the timed region."""
+    import numpy as np
+    import torch
+
+    import paper_2006_04593_amd as fss
+    from paper_2006_04593_amd import workloads as W
+
+    n, B = N_BITS, 64 * 112 * 112
+    rng = np.random.default_rng(W.BASE_SEED + 3)
+    y = W.fixed_point_normal(rng, B)
+    g = W.gen_inputs(rng, n, B)
+    ri = W.relu_inputs(rng, n, y)
+
+    def T(a):
+        return torch.from_numpy(a.view(np.int32) if a.dtype == np.uint32 else a).to(dev)
+
+    keys = [torch.empty(fss.cmp_key_bytes(n, B), dtype=torch.uint8, device=dev) for _ in range(2)]
+    fss.cmp_gen(n, B, T(g.alpha), T(g.r), T(g.seed0), T(g.seed1), keys[0], keys[1])
+    ys, ta, tb, tc = ([T(p[j]) for j in (0, 1)] for p in (ri.y_share, ri.tri_a, ri.tri_b, ri.tri_c))
+    buf = lambda: [torch.empty(B, dtype=torch.int32, device=dev) for _ in range(2)]
+    masked, delta, eps, z = buf(), buf(), buf(), buf()
+    stream = torch.cuda.current_stream()
+    open_ms = []
+
+    def step(timed):
+        for j in (0, 1):
+            fss.sign_mask(n, B, keys[j], ys[j], masked[j], stream=stream)
+        for j in (0, 1):
+            if timed:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+            fss.relu_open(j, n, B, keys[j], masked[0], masked[1], ys[j], ta[j], tb[j], delta[j], eps[j], stream=stream)
+            if timed:
+                e1.record(stream)
+                open_ms.append((e0, e1))
+        for j in (0, 1):
+            fss.relu_finish(j, n, B, delta[0], delta[1], eps[0], eps[1], ta[j], tb[j], tc[j], z[j], stream=stream)
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    rec = (z[0] + z[1]).cpu().numpy().view(np.uint32)
+    x = (masked[0] + masked[1]).cpu().numpy().view(np.uint32)
+    le = (x <= g.alpha)
+    assert np.array_equal(rec, np.where(le, 0, y & 0xFFFFFFFF).astype(np.uint32)), "ReLU reconstruction failed"
+    ms = sum(a.elapsed_time(b) for a, b in open_ms) / len(open_ms)
+    lds_gbs = B * LDS_BYTES_PER_EVAL / (ms * 1e-3) / 1e9
+    return {
+        "metric": "shared ReLU elements/sec per party (n=32, lambda=128)",
+        "value": B / (ms * 1e-3), "unit": "elements/s/party", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32", "data": "synthetic",
+        "config": {"workload": "ReLU layer 64x112x112 = 802816 fixed-point activations: Sign mask + fused comparison/open "
+                               "round + finish, both parties", "batch": B, "n": n, "lambda": 128},
+        "relu_open_ms": ms,
+        "roofline": {"bound": "lds", "kernel": "eval_kernel<cmp, relu-open>", "achieved": lds_gbs, "peak": PEAK_LDS_GBS,
+                     "unit": "GB/s", "frac": lds_gbs / PEAK_LDS_GBS, "traffic": None},
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -73,6 +141,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--batch", type=int, default=1 << 22, help="elements per step (default: the 2^22 configuration)")
     ap.add_argument("--cpu-sample", type=int, default=1 << 18, help="elements for the oracle timing; 0 skips it")
+    ap.add_argument("--workload", choices=["large", "relu"], default="large",
+                    help="large: the headline 2^22 comparison Gen+Eval step; relu: one shared ReLU layer of "
+                         "64x112x112 activations (Sign mask, fused comparison+open round, finish) per party")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also launch one plain elementwise copy over 1 GiB, so that a rocprofv3 --pmc run of this "
                          "command holds the counter's reading for a kernel of known traffic")
@@ -91,6 +162,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.workload == "relu":
+        print(json.dumps(relu_layer_bench(args, dev)))
+        return
     B, n = args.batch, N_BITS
     w = W.uniform_workload("cmp", n, B, seed=W.BASE_SEED + 5, name="config5")
     g = w.gen

@@ -112,6 +112,35 @@ int fss_eq_gen(int n, size_t batch, const uint32_t *d_alpha, const uint32_t *d_a
 int fss_eq_eval(int party, int n, size_t batch, const void *d_key, const uint32_t *d_x,
                 uint32_t *d_out, fss_stream_t stream);
 
+/* ---- the steps around the comparison: Sign protocol and ReLU ---------------------------
+ *
+ * Sign protocol, Algorithm 5 of the paper, for shared inputs [[y]]: each party publishes
+ * [[y]]_j + [[alpha]]_j (fss_sign_mask; [[alpha]]_j is the first plane of its key), both add
+ * the two published vectors to x = y + alpha and evaluate the comparison key on it
+ * (fss_sign_eval, reveal fused into the evaluation kernel).  The result is a share of
+ * 1{y <= 0} except with probability |y| / 2^n (section 3.2.2).
+ *
+ * ReLU, section 4.2: ReLU(y) = y . (1 - 1{y <= 0}), the comparison followed by ONE pointwise
+ * product of shared values with a multiplication triple ([[a]], [[b]], [[c]] = [[a.b]]) as in
+ * the paper's MatMul paragraph; 2 rounds, 3 values per element (Table 2).
+ *   round 1: publish fss_sign_mask's output;
+ *   round 2: fss_relu_open evaluates the comparison and directly forms the party's messages
+ *            delta_j = [[y]]_j - [[a]]_j and eps_j = ([j = 0] - [[1{y<=0}]]_j) - [[b]]_j;
+ *   then     fss_relu_finish: [[ReLU(y)]]_j = delta.[[b]]_j + eps.[[a]]_j + [[c]]_j (+ delta.eps
+ *            for party 0), delta = delta_0 + delta_1, eps = eps_0 + eps_1.
+ * All arrays are [batch] u32 device arrays of that party unless they carry the other party's
+ * index (published values).  The exchange between the parties is the caller's business. */
+int fss_sign_mask(int n, size_t batch, const void *d_key, const uint32_t *d_y_share, uint32_t *d_masked,
+                  fss_stream_t stream);
+int fss_sign_eval(int party, int n, size_t batch, const void *d_key, const uint32_t *d_masked0,
+                  const uint32_t *d_masked1, uint32_t *d_out, fss_stream_t stream);
+int fss_relu_open(int party, int n, size_t batch, const void *d_key, const uint32_t *d_masked0,
+                  const uint32_t *d_masked1, const uint32_t *d_y_share, const uint32_t *d_tri_a,
+                  const uint32_t *d_tri_b, uint32_t *d_delta, uint32_t *d_eps, fss_stream_t stream);
+int fss_relu_finish(int party, int n, size_t batch, const uint32_t *d_delta0, const uint32_t *d_delta1,
+                    const uint32_t *d_eps0, const uint32_t *d_eps1, const uint32_t *d_tri_a,
+                    const uint32_t *d_tri_b, const uint32_t *d_tri_c, uint32_t *d_out, fss_stream_t stream);
+
 /* Text for a return code (static storage, never NULL). */
 const char *fss_strerror(int code);
 

@@ -15,4 +15,8 @@ from .binding import (  # noqa: F401
     eq_key_bytes,
     lib,
     library_path,
+    relu_finish,
+    relu_open,
+    sign_eval,
+    sign_mask,
 )

@@ -14,7 +14,7 @@ _SO = os.path.join(_HERE, "libfss_mi355.so")
 _lib: Optional[C.CDLL] = None
 
 EXPORTS = ("fss_cmp_key_bytes", "fss_eq_key_bytes", "fss_cmp_gen", "fss_cmp_eval", "fss_eq_gen", "fss_eq_eval",
-           "fss_strerror", "fss_last_hip_error")
+           "fss_sign_mask", "fss_sign_eval", "fss_relu_open", "fss_relu_finish", "fss_strerror", "fss_last_hip_error")
 
 HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -78,6 +78,12 @@ def lib() -> C.CDLL:
         for name in ("fss_cmp_eval", "fss_eq_eval"):
             getattr(L, name).argtypes = [i, i, sz, vp, vp, vp, vp]
             getattr(L, name).restype = i
+        L.fss_sign_mask.argtypes = [i, sz, vp, vp, vp, vp]
+        L.fss_sign_eval.argtypes = [i, i, sz, vp, vp, vp, vp, vp]
+        L.fss_relu_open.argtypes = [i, i, sz, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.fss_relu_finish.argtypes = [i, i, sz, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        for name in ("fss_sign_mask", "fss_sign_eval", "fss_relu_open", "fss_relu_finish"):
+            getattr(L, name).restype = i
         L.fss_strerror.argtypes = [i]
         L.fss_strerror.restype = C.c_char_p
         L.fss_last_hip_error.argtypes = []
@@ -133,3 +139,23 @@ def cmp_eval(party: int, n: int, batch: int, d_key, d_x, d_out, stream=None) -> 
 
 def eq_eval(party: int, n: int, batch: int, d_key, d_x, d_out, stream=None) -> None:
     _check(lib().fss_eq_eval(party, n, batch, _ptr(d_key), _ptr(d_x), _ptr(d_out), _stream(stream)))
+
+
+def sign_mask(n: int, batch: int, d_key, d_y_share, d_masked, stream=None) -> None:
+    _check(lib().fss_sign_mask(n, batch, _ptr(d_key), _ptr(d_y_share), _ptr(d_masked), _stream(stream)))
+
+
+def sign_eval(party: int, n: int, batch: int, d_key, d_masked0, d_masked1, d_out, stream=None) -> None:
+    _check(lib().fss_sign_eval(party, n, batch, _ptr(d_key), _ptr(d_masked0), _ptr(d_masked1), _ptr(d_out), _stream(stream)))
+
+
+def relu_open(party: int, n: int, batch: int, d_key, d_masked0, d_masked1, d_y_share, d_tri_a, d_tri_b, d_delta, d_eps,
+              stream=None) -> None:
+    _check(lib().fss_relu_open(party, n, batch, _ptr(d_key), _ptr(d_masked0), _ptr(d_masked1), _ptr(d_y_share), _ptr(d_tri_a),
+                               _ptr(d_tri_b), _ptr(d_delta), _ptr(d_eps), _stream(stream)))
+
+
+def relu_finish(party: int, n: int, batch: int, d_delta0, d_delta1, d_eps0, d_eps1, d_tri_a, d_tri_b, d_tri_c, d_out,
+                stream=None) -> None:
+    _check(lib().fss_relu_finish(party, n, batch, _ptr(d_delta0), _ptr(d_delta1), _ptr(d_eps0), _ptr(d_eps1), _ptr(d_tri_a),
+                                 _ptr(d_tri_b), _ptr(d_tri_c), _ptr(d_out), _stream(stream)))

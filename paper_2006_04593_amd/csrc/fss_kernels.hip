@@ -19,10 +19,23 @@ namespace fss {
 
 __device__ __forceinline__ uint32_t ring_mask(int n) { return n == 32 ? 0xffffffffu : ((1u << n) - 1u); }
 
+// What the evaluation kernel reads as its public input and writes as its result.
+//   kPlain:    x given; out = share of f(x)                                   (Algorithms 2, 4)
+//   kSign:     x = x[e] + x2[e] (the two published masked shares)              (Algorithm 5)
+//   kReluOpen: as kSign, then the party's messages for the ReLU product: with w the share of
+//              1{y <= 0} and v = [party = 0] - w the share of 1{y > 0},
+//              out = delta_j = [[y]]_j - [[a]]_j,  out2 = eps_j = v - [[b]]_j   (section 4.2)
+enum EvalMode { kPlain = 0, kSign = 1, kReluOpen = 2 };
+
 struct EvalArgs {
     const uint8_t *key;
     const uint32_t *x;
+    const uint32_t *x2;        // second masked share (kSign, kReluOpen)
     uint32_t *out;
+    uint32_t *out2;            // eps_j (kReluOpen)
+    const uint32_t *y_share;   // [[y]]_j (kReluOpen)
+    const uint32_t *tri_a;     // [[a]]_j (kReluOpen)
+    const uint32_t *tri_b;     // [[b]]_j (kReluOpen)
     size_t batch;
     int n;
     int party;
@@ -43,7 +56,7 @@ struct GenArgs {
 // Eval: Algorithm 2 (CMP = false) and Algorithm 4 (CMP = true)
 // ------------------------------------------------------------------------------------
 
-template <bool CMP>
+template <bool CMP, int MODE>
 __global__ __launch_bounds__(kThreads) void eval_kernel(EvalArgs a)
 {
     extern __shared__ uint32_t lds[];
@@ -59,8 +72,14 @@ __global__ __launch_bounds__(kThreads) void eval_kernel(EvalArgs a)
     const uint32_t *leaf_p = reinterpret_cast<const uint32_t *>(a.key + k.leaf);
     const uint32_t *last_p = reinterpret_cast<const uint32_t *>(a.key + k.last);
 
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < a.batch; e += stride) {
+    // Work unit = a 64-element tile per wavefront.  Tile t of pass p goes to wavefront w of
+    // workgroup g with t = (p * waves_per_group + w) * groups + g, so that a ragged last pass
+    // leaves one busy wavefront on many CUs rather than a few fully loaded CUs.
+    const size_t tiles = (a.batch + 63) / 64;
+    const size_t tile_stride = (size_t)(blockDim.x >> 6) * gridDim.x;
+    for (size_t tile = (size_t)(threadIdx.x >> 6) * gridDim.x + blockIdx.x; tile < tiles; tile += tile_stride) {
+        const size_t e = tile * 64 + (threadIdx.x & 63u);
+        if (e >= a.batch) continue;
         uint4 sv = seed_p[e];
         uint32_t s[4] = { sv.x & ~1u, sv.y, sv.z, sv.w };
         uint32_t t = (uint32_t)a.party;                 // t^(1) = j
@@ -72,7 +91,9 @@ __global__ __launch_bounds__(kThreads) void eval_kernel(EvalArgs a)
             uint2 c = reinterpret_cast<const uint2 *>(a.key + k.ctrl)[e];
             tcw[0] = c.x; tcw[1] = c.y;
         }
-        const uint32_t x = a.x[e] & mask;
+        uint32_t xin = a.x[e];
+        if constexpr (MODE != kPlain) xin += a.x2[e];    // the reveal: x = alpha + y
+        const uint32_t x = xin & mask;
         uint32_t acc = 0;
 
         // correction words are fetched one level ahead of their use
@@ -121,7 +142,36 @@ __global__ __launch_bounds__(kThreads) void eval_kernel(EvalArgs a)
         }
         acc += (t ? last_p[e] : 0u) + (s[3] & mask);     // out_{n+1}
         if (a.party) acc = 0u - acc;
-        a.out[e] = acc & mask;
+        acc &= mask;
+        if constexpr (MODE == kReluOpen) {
+            const uint32_t v = ((a.party ? 0u : 1u) - acc) & mask;     // share of 1{y > 0}
+            a.out[e] = (a.y_share[e] - a.tri_a[e]) & mask;
+            a.out2[e] = (v - a.tri_b[e]) & mask;
+        } else {
+            a.out[e] = acc;
+        }
+    }
+}
+
+// [[y]]_j + [[alpha]]_j: the value party j publishes in the Sign protocol (Algorithm 5)
+__global__ void sign_mask_kernel(const uint32_t *alpha_share, const uint32_t *y_share, uint32_t *masked, size_t batch, uint32_t mask)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < batch; e += stride)
+        masked[e] = (y_share[e] + alpha_share[e]) & mask;
+}
+
+// [[u.v]]_j = delta.[[b]]_j + eps.[[a]]_j + [[c]]_j (+ delta.eps for party 0), section 4.2
+__global__ void relu_finish_kernel(const uint32_t *d0, const uint32_t *d1, const uint32_t *e0, const uint32_t *e1,
+                                   const uint32_t *ta, const uint32_t *tb, const uint32_t *tc, uint32_t *out,
+                                   size_t batch, uint32_t mask, int party)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < batch; e += stride) {
+        const uint32_t delta = d0[e] + d1[e], eps = e0[e] + e1[e];
+        uint32_t z = delta * tb[e] + eps * ta[e] + tc[e];
+        if (party == 0) z += delta * eps;
+        out[e] = z & mask;
     }
 }
 
@@ -140,8 +190,11 @@ __global__ __launch_bounds__(kThreads) void gen_kernel(GenArgs a)
     const int n = a.n;
     const uint32_t mask = ring_mask(n);
 
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < k.bp; e += stride) {
+    // same tile-to-wavefront assignment as the evaluation kernel; the padded batch is whole tiles
+    const size_t tiles = k.bp / 64;
+    const size_t tile_stride = (size_t)(blockDim.x >> 6) * gridDim.x;
+    for (size_t tile = (size_t)(threadIdx.x >> 6) * gridDim.x + blockIdx.x; tile < tiles; tile += tile_stride) {
+        const size_t e = tile * 64 + (threadIdx.x & 63u);
         if (e >= a.batch) {
             // padding elements: defined (zero) contents in every plane
 #pragma unroll
@@ -297,9 +350,10 @@ static int prepare_device(DeviceInfo *info)
         if (err == hipSuccess) err = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (err != hipSuccess) { g_last_hip_error = (int)err; return FSS_ELAUNCH; }
         if ((uint32_t)lds < kLdsBytes) { cache[dev].ok = -1; g_last_hip_error = 0; return FSS_EDEVICE; }
-        const void *fns[4] = { (const void *)eval_kernel<true>, (const void *)eval_kernel<false>,
+        const void *fns[6] = { (const void *)eval_kernel<true, kPlain>, (const void *)eval_kernel<false, kPlain>,
+                               (const void *)eval_kernel<true, kSign>, (const void *)eval_kernel<true, kReluOpen>,
                                (const void *)gen_kernel<true>, (const void *)gen_kernel<false> };
-        for (int i = 0; i < 4; i++) {
+        for (int i = 0; i < 6; i++) {
             err = hipFuncSetAttribute(fns[i], hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
             if (err != hipSuccess) { g_last_hip_error = (int)err; return FSS_ELAUNCH; }
         }
@@ -319,20 +373,19 @@ struct LaunchShape {
     unsigned grid, threads;
 };
 
-// One workgroup per CU (its tables take 128 KiB of the CU's LDS).  Large batches: 1024 threads
-// per workgroup and a grid-stride loop.  Batches that would leave CUs idle at that size are
-// spread over all CUs with fewer wavefronts per workgroup instead.
+// One workgroup per CU (its tables take 128 KiB of the CU's LDS); the kernels loop over
+// 64-element tiles.  Every CU gets a workgroup as soon as there are that many tiles, with just
+// enough wavefronts to cover its share (16 at most).
 static LaunchShape shape_for(size_t elems, const DeviceInfo &d)
 {
     const size_t cus = (size_t)d.cus;
-    size_t threads = (elems + cus - 1) / cus;                  // elements per CU if spread evenly
-    threads = (threads + 63) / 64 * 64;
-    if (threads < 64) threads = 64;
-    if (threads > (size_t)kThreads) threads = kThreads;
-    size_t tiles = (elems + threads - 1) / threads;
+    const size_t tiles = (elems + 63) / 64;
+    const size_t groups = tiles < cus ? tiles : cus;
+    size_t waves = (tiles + groups - 1) / groups;
+    if (waves > (size_t)kThreads / 64) waves = kThreads / 64;
     LaunchShape s;
-    s.threads = (unsigned)threads;
-    s.grid = (unsigned)(tiles < cus ? tiles : cus);
+    s.threads = (unsigned)(waves * 64);
+    s.grid = (unsigned)groups;
     return s;
 }
 
@@ -370,24 +423,38 @@ static int gen_common(bool cmp, int n, size_t batch, const uint32_t *d_alpha, co
     return check_launch();
 }
 
-static int eval_common(bool cmp, int party, int n, size_t batch, const void *d_key, const uint32_t *d_x,
-                       uint32_t *d_out, fss_stream_t stream)
+static int eval_common(bool cmp, int mode, int party, int n, size_t batch, const void *d_key, const uint32_t *d_x,
+                       const uint32_t *d_x2, uint32_t *d_out, uint32_t *d_out2, const uint32_t *d_y, const uint32_t *d_ta,
+                       const uint32_t *d_tb, fss_stream_t stream)
 {
     if (bad_n(n) || (party != 0 && party != 1)) return FSS_EINVAL;
     if (batch == 0) return FSS_OK;
     if (!d_key || !d_x || !d_out) return FSS_EINVAL;
     if (misaligned(d_key, 256) || misaligned(d_x, 4) || misaligned(d_out, 4)) return FSS_EINVAL;
+    if (mode != kPlain && (!d_x2 || misaligned(d_x2, 4))) return FSS_EINVAL;
+    if (mode == kReluOpen && (!d_out2 || !d_y || !d_ta || !d_tb || misaligned(d_out2, 4) || misaligned(d_y, 4) ||
+                              misaligned(d_ta, 4) || misaligned(d_tb, 4)))
+        return FSS_EINVAL;
     DeviceInfo dev;
     int rc = prepare_device(&dev);
     if (rc != FSS_OK) return rc;
     EvalArgs a;
-    a.key = static_cast<const uint8_t *>(d_key); a.x = d_x; a.out = d_out;
+    a.key = static_cast<const uint8_t *>(d_key); a.x = d_x; a.x2 = d_x2; a.out = d_out; a.out2 = d_out2;
+    a.y_share = d_y; a.tri_a = d_ta; a.tri_b = d_tb;
     a.batch = batch; a.n = n; a.party = party;
     const LaunchShape ls = shape_for(batch, dev);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (cmp) hipLaunchKernelGGL(eval_kernel<true>, dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
-    else hipLaunchKernelGGL(eval_kernel<false>, dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
+    if (!cmp) hipLaunchKernelGGL((eval_kernel<false, kPlain>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
+    else if (mode == kPlain) hipLaunchKernelGGL((eval_kernel<true, kPlain>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
+    else if (mode == kSign) hipLaunchKernelGGL((eval_kernel<true, kSign>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
+    else hipLaunchKernelGGL((eval_kernel<true, kReluOpen>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
     return check_launch();
+}
+
+static unsigned elementwise_grid(size_t batch)
+{
+    size_t g = (batch + 255) / 256;
+    return (unsigned)(g < 4096 ? g : 4096);
 }
 
 }  // namespace fss
@@ -413,13 +480,57 @@ int fss_eq_gen(int n, size_t batch, const uint32_t *d_alpha, const uint32_t *d_a
 int fss_cmp_eval(int party, int n, size_t batch, const void *d_key, const uint32_t *d_x, uint32_t *d_out,
                  fss_stream_t stream)
 {
-    return fss::eval_common(true, party, n, batch, d_key, d_x, d_out, stream);
+    return fss::eval_common(true, fss::kPlain, party, n, batch, d_key, d_x, nullptr, d_out, nullptr, nullptr, nullptr, nullptr, stream);
 }
 
 int fss_eq_eval(int party, int n, size_t batch, const void *d_key, const uint32_t *d_x, uint32_t *d_out,
                 fss_stream_t stream)
 {
-    return fss::eval_common(false, party, n, batch, d_key, d_x, d_out, stream);
+    return fss::eval_common(false, fss::kPlain, party, n, batch, d_key, d_x, nullptr, d_out, nullptr, nullptr, nullptr, nullptr, stream);
+}
+
+int fss_sign_mask(int n, size_t batch, const void *d_key, const uint32_t *d_y_share, uint32_t *d_masked, fss_stream_t stream)
+{
+    using namespace fss;
+    if (bad_n(n)) return FSS_EINVAL;
+    if (batch == 0) return FSS_OK;
+    if (!d_key || !d_y_share || !d_masked) return FSS_EINVAL;
+    if (misaligned(d_key, 256) || misaligned(d_y_share, 4) || misaligned(d_masked, 4)) return FSS_EINVAL;
+    const uint32_t *alpha_share = reinterpret_cast<const uint32_t *>(static_cast<const uint8_t *>(d_key) + key_layout(true, n, batch).alpha_share);
+    const uint32_t mask = n == 32 ? 0xffffffffu : ((1u << n) - 1u);
+    hipLaunchKernelGGL(sign_mask_kernel, dim3(elementwise_grid(batch)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       alpha_share, d_y_share, d_masked, batch, mask);
+    return check_launch();
+}
+
+int fss_sign_eval(int party, int n, size_t batch, const void *d_key, const uint32_t *d_masked0, const uint32_t *d_masked1,
+                  uint32_t *d_out, fss_stream_t stream)
+{
+    return fss::eval_common(true, fss::kSign, party, n, batch, d_key, d_masked0, d_masked1, d_out, nullptr, nullptr, nullptr, nullptr, stream);
+}
+
+int fss_relu_open(int party, int n, size_t batch, const void *d_key, const uint32_t *d_masked0, const uint32_t *d_masked1,
+                  const uint32_t *d_y_share, const uint32_t *d_tri_a, const uint32_t *d_tri_b, uint32_t *d_delta,
+                  uint32_t *d_eps, fss_stream_t stream)
+{
+    return fss::eval_common(true, fss::kReluOpen, party, n, batch, d_key, d_masked0, d_masked1, d_delta, d_eps, d_y_share, d_tri_a,
+                            d_tri_b, stream);
+}
+
+int fss_relu_finish(int party, int n, size_t batch, const uint32_t *d_delta0, const uint32_t *d_delta1, const uint32_t *d_eps0,
+                    const uint32_t *d_eps1, const uint32_t *d_tri_a, const uint32_t *d_tri_b, const uint32_t *d_tri_c,
+                    uint32_t *d_out, fss_stream_t stream)
+{
+    using namespace fss;
+    if (bad_n(n) || (party != 0 && party != 1)) return FSS_EINVAL;
+    if (batch == 0) return FSS_OK;
+    const void *ptrs[8] = { d_delta0, d_delta1, d_eps0, d_eps1, d_tri_a, d_tri_b, d_tri_c, d_out };
+    for (int i = 0; i < 8; i++)
+        if (!ptrs[i] || misaligned(ptrs[i], 4)) return FSS_EINVAL;
+    const uint32_t mask = n == 32 ? 0xffffffffu : ((1u << n) - 1u);
+    hipLaunchKernelGGL(relu_finish_kernel, dim3(elementwise_grid(batch)), dim3(256), 0, static_cast<hipStream_t>(stream), d_delta0,
+                       d_delta1, d_eps0, d_eps1, d_tri_a, d_tri_b, d_tri_c, d_out, batch, mask, party);
+    return check_launch();
 }
 
 const char *fss_strerror(int code)

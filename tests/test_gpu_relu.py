@@ -1,0 +1,121 @@
+"""GPU parity for the steps around the comparison: Sign protocol (Algorithm 5) and the fused
+ReLU round (section 4.2), through the C ABI, bit-exact against the oracle."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2006_04593_amd as fss
+from paper_2006_04593_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+def dev():
+    return torch.device("cuda:0")
+
+
+def to_dev(a):
+    if a.dtype == np.uint32:
+        a = a.view(np.int32)
+    return torch.from_numpy(np.ascontiguousarray(a)).to(dev())
+
+
+def u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+def empty_u32(batch):
+    return torch.full((batch,), -1, dtype=torch.int32, device=dev())
+
+
+def gpu_relu_layer(n, g, ri):
+    """Both parties on the one GPU; the 'network' is the test handing arrays across."""
+    batch = g.batch
+    nbytes = fss.cmp_key_bytes(n, batch)
+    keys = [torch.zeros(nbytes, dtype=torch.uint8, device=dev()) for _ in range(2)]
+    fss.cmp_gen(n, batch, to_dev(g.alpha), to_dev(g.r), to_dev(g.seed0), to_dev(g.seed1), keys[0], keys[1])
+    ys = [to_dev(ri.y_share[j]) for j in (0, 1)]
+    ta = [to_dev(ri.tri_a[j]) for j in (0, 1)]
+    tb = [to_dev(ri.tri_b[j]) for j in (0, 1)]
+    tc = [to_dev(ri.tri_c[j]) for j in (0, 1)]
+    masked = [empty_u32(batch) for _ in range(2)]
+    for j in (0, 1):
+        fss.sign_mask(n, batch, keys[j], ys[j], masked[j])
+    sign = [empty_u32(batch) for _ in range(2)]
+    delta = [empty_u32(batch) for _ in range(2)]
+    eps = [empty_u32(batch) for _ in range(2)]
+    for j in (0, 1):
+        fss.sign_eval(j, n, batch, keys[j], masked[0], masked[1], sign[j])
+        fss.relu_open(j, n, batch, keys[j], masked[0], masked[1], ys[j], ta[j], tb[j], delta[j], eps[j])
+    z = [empty_u32(batch) for _ in range(2)]
+    for j in (0, 1):
+        fss.relu_finish(j, n, batch, delta[0], delta[1], eps[0], eps[1], ta[j], tb[j], tc[j], z[j])
+    torch.cuda.synchronize()
+    return dict(keys=keys, masked=[u32(m) for m in masked], sign=[u32(s) for s in sign], delta=[u32(d) for d in delta],
+                eps=[u32(e) for e in eps], z=[u32(v) for v in z])
+
+
+def oracle_relu_layer(n, g, ri, idx=None):
+    if idx is not None:
+        g = W.GenInputs(n=n, alpha=g.alpha[idx], r=g.r[idx], seed0=g.seed0[idx], seed1=g.seed1[idx])
+        ri = W.ReluInputs(*[tuple(a[idx] for a in pair) for pair in (ri.y_share, ri.tri_a, ri.tri_b, ri.tri_c)])
+    k = oracle.gen("cmp", n, g.alpha, g.r, g.seed0, g.seed1)
+    masked = [oracle.sign_mask(n, k[j], ri.y_share[j]) for j in (0, 1)]
+    sign = [oracle.sign_eval(j, n, k[j], masked[0], masked[1]) for j in (0, 1)]
+    op = [oracle.relu_open(j, n, k[j], masked[0], masked[1], ri.y_share[j], ri.tri_a[j], ri.tri_b[j]) for j in (0, 1)]
+    z = [oracle.relu_finish(j, n, op[0][0], op[1][0], op[0][1], op[1][1], ri.tri_a[j], ri.tri_b[j], ri.tri_c[j]) for j in (0, 1)]
+    return dict(masked=masked, sign=sign, delta=[op[0][0], op[1][0]], eps=[op[0][1], op[1][1]], z=z)
+
+
+@pytest.mark.parametrize("n,batch", [(32, 1), (32, 777), (32, 4096), (12, 4096), (8, 256), (16, 1000)])
+def test_relu_layer_matches_oracle(n, batch):
+    print(f"case relu n={n} batch={batch}", flush=True)
+    rng = np.random.default_rng(n * 1000 + batch)
+    if batch == (1 << n):
+        y = np.arange(batch, dtype=np.int64)                  # every value of the ring
+    else:
+        y = W.fixed_point_normal(rng, batch, frac_bits=min(12, n - 3))
+    g = W.gen_inputs(rng, n, batch)
+    ri = W.relu_inputs(rng, n, y)
+    got = gpu_relu_layer(n, g, ri)
+    want = oracle_relu_layer(n, g, ri)
+    for name in ("masked", "sign", "delta", "eps", "z"):
+        for j in (0, 1):
+            assert np.array_equal(got[name][j], want[name][j]), (name, j)
+    mask = W.ring_mask(n)
+    x = (got["masked"][0] + got["masked"][1]) & np.uint32(mask)
+    le = (x <= g.alpha).astype(np.uint64)
+    rec = (got["z"][0] + got["z"][1]) & np.uint32(mask)
+    assert np.array_equal(rec, ((y.astype(np.uint64) * (1 - le)) & mask).astype(np.uint32))
+
+
+def test_relu_layer_config3_shape():
+    """64 x 112 x 112 activations: the fused round at the benchmark size; the oracle recomputes a
+    seeded sample, the ReLU identity is checked on every element."""
+    n, batch = 32, 64 * 112 * 112
+    rng = np.random.default_rng(W.BASE_SEED + 3)
+    y = W.fixed_point_normal(rng, batch)
+    g = W.gen_inputs(rng, n, batch)
+    ri = W.relu_inputs(rng, n, y)
+    got = gpu_relu_layer(n, g, ri)
+    rec = got["z"][0] + got["z"][1]
+    fail = (got["sign"][0] + got["sign"][1]) != (y <= 0)
+    assert fail.sum() <= 8                                    # Sign wrap-around, |y| / 2^32 each
+    want = (np.maximum(y, 0) & 0xFFFFFFFF).astype(np.uint32)
+    assert np.array_equal(rec[~fail], want[~fail])
+    idx = np.sort(np.random.default_rng(33).choice(batch, size=4096, replace=False))
+    idx[0], idx[-1] = 0, batch - 1
+    ref = oracle_relu_layer(n, g, ri, idx)
+    for name in ("masked", "sign", "delta", "eps", "z"):
+        for j in (0, 1):
+            assert np.array_equal(got[name][j][idx], ref[name][j]), (name, j)
+
+
+def test_bad_arguments():
+    with pytest.raises(fss.FssError):
+        fss.relu_open(0, 32, 8, None, None, None, None, None, None, None, None)
+    with pytest.raises(fss.FssError):
+        fss.sign_eval(2, 32, 0, None, None, None, None)
+    fss.relu_finish(1, 32, 0, None, None, None, None, None, None, None, None)
+    torch.cuda.synchronize()
