@@ -141,6 +141,29 @@ int fss_relu_finish(int party, int n, size_t batch, const uint32_t *d_delta0, co
                     const uint32_t *d_eps0, const uint32_t *d_eps1, const uint32_t *d_tri_a,
                     const uint32_t *d_tri_b, const uint32_t *d_tri_c, uint32_t *d_out, fss_stream_t stream);
 
+/* ---- keys kept in host memory, imported during the online phase --------------------------
+ *
+ * The paper notes (section 5.2) that device memory for keys limits the batch size and that
+ * keeping keys on the host and importing them online would lift that.  Chunked host layout:
+ * the batch is cut into consecutive chunks of `chunk` elements (the last may be shorter);
+ * chunk c is an ordinary key buffer for its own elements, fss_cmp_key_bytes(n, len_c) bytes,
+ * and the chunks follow each other without gaps in `h_key_chunks` (PINNED host memory,
+ * allocated by the caller with hipHostMalloc or torch's pin_memory; pageable memory works but
+ * serialises the copies).  fss_cmp_chunked_key_bytes gives the total size.
+ *
+ * fss_cmp_eval_streamed copies chunk c+1 host-to-device on `copy_stream` into one half of
+ * `d_staging` while chunk c is evaluated on `stream` out of the other half, ordering the two
+ * with events it creates and destroys inside the call.  d_staging: device memory,
+ * 2 * fss_cmp_key_bytes(n, chunk) bytes, 256-byte aligned.  chunk must be a multiple of 64.
+ * Unlike the other entry points this one BLOCKS until the last chunk has been evaluated (it has
+ * to recycle the staging halves), and `copy_stream` must differ from `stream`.  Results are
+ * identical to fss_cmp_eval on the same keys.  The rate is bounded by the host link:
+ * 808 bytes per element at n = 32. */
+size_t fss_cmp_chunked_key_bytes(int n, size_t batch, size_t chunk);
+int fss_cmp_eval_streamed(int party, int n, size_t batch, size_t chunk, const void *h_key_chunks,
+                          const uint32_t *d_x, uint32_t *d_out, void *d_staging,
+                          fss_stream_t copy_stream, fss_stream_t stream);
+
 /* Text for a return code (static storage, never NULL). */
 const char *fss_strerror(int code);
 

@@ -7,7 +7,9 @@ library has not been built, importing `binding` functions raises.
 from .binding import (  # noqa: F401
     FssError,
     build,
+    cmp_chunked_key_bytes,
     cmp_eval,
+    cmp_eval_streamed,
     cmp_gen,
     cmp_key_bytes,
     eq_eval,

@@ -14,7 +14,8 @@ _SO = os.path.join(_HERE, "libfss_mi355.so")
 _lib: Optional[C.CDLL] = None
 
 EXPORTS = ("fss_cmp_key_bytes", "fss_eq_key_bytes", "fss_cmp_gen", "fss_cmp_eval", "fss_eq_gen", "fss_eq_eval",
-           "fss_sign_mask", "fss_sign_eval", "fss_relu_open", "fss_relu_finish", "fss_strerror", "fss_last_hip_error")
+           "fss_sign_mask", "fss_sign_eval", "fss_relu_open", "fss_relu_finish", "fss_cmp_chunked_key_bytes",
+           "fss_cmp_eval_streamed", "fss_strerror", "fss_last_hip_error")
 
 HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -84,6 +85,10 @@ def lib() -> C.CDLL:
         L.fss_relu_finish.argtypes = [i, i, sz, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         for name in ("fss_sign_mask", "fss_sign_eval", "fss_relu_open", "fss_relu_finish"):
             getattr(L, name).restype = i
+        L.fss_cmp_chunked_key_bytes.argtypes = [i, sz, sz]
+        L.fss_cmp_chunked_key_bytes.restype = sz
+        L.fss_cmp_eval_streamed.argtypes = [i, i, sz, sz, vp, vp, vp, vp, vp, vp]
+        L.fss_cmp_eval_streamed.restype = i
         L.fss_strerror.argtypes = [i]
         L.fss_strerror.restype = C.c_char_p
         L.fss_last_hip_error.argtypes = []
@@ -159,3 +164,14 @@ def relu_finish(party: int, n: int, batch: int, d_delta0, d_delta1, d_eps0, d_ep
                 stream=None) -> None:
     _check(lib().fss_relu_finish(party, n, batch, _ptr(d_delta0), _ptr(d_delta1), _ptr(d_eps0), _ptr(d_eps1), _ptr(d_tri_a),
                                  _ptr(d_tri_b), _ptr(d_tri_c), _ptr(d_out), _stream(stream)))
+
+
+def cmp_chunked_key_bytes(n: int, batch: int, chunk: int) -> int:
+    return int(lib().fss_cmp_chunked_key_bytes(n, batch, chunk))
+
+
+def cmp_eval_streamed(party: int, n: int, batch: int, chunk: int, h_key_chunks, d_x, d_out, d_staging, copy_stream,
+                      stream=None) -> None:
+    """fss_cmp_eval_streamed: h_key_chunks is a pinned HOST tensor in the chunked layout."""
+    _check(lib().fss_cmp_eval_streamed(party, n, batch, chunk, _ptr(h_key_chunks), _ptr(d_x), _ptr(d_out), _ptr(d_staging),
+                                       _stream(copy_stream), _stream(stream)))

@@ -533,6 +533,60 @@ int fss_relu_finish(int party, int n, size_t batch, const uint32_t *d_delta0, co
     return check_launch();
 }
 
+size_t fss_cmp_chunked_key_bytes(int n, size_t batch, size_t chunk)
+{
+    if (fss::bad_n(n) || chunk == 0 || chunk % 64 != 0) return 0;
+    const size_t full = batch / chunk, rest = batch % chunk;
+    return full * fss::key_layout(true, n, chunk).total + (rest ? fss::key_layout(true, n, rest).total : 0);
+}
+
+int fss_cmp_eval_streamed(int party, int n, size_t batch, size_t chunk, const void *h_key_chunks, const uint32_t *d_x,
+                          uint32_t *d_out, void *d_staging, fss_stream_t copy_stream, fss_stream_t stream)
+{
+    using namespace fss;
+    if (bad_n(n) || (party != 0 && party != 1) || chunk == 0 || chunk % 64 != 0) return FSS_EINVAL;
+    if (batch == 0) return FSS_OK;
+    if (!h_key_chunks || !d_x || !d_out || !d_staging || misaligned(d_staging, 256) || misaligned(d_x, 4) || misaligned(d_out, 4))
+        return FSS_EINVAL;
+    if (copy_stream == stream) return FSS_EINVAL;
+    hipStream_t cs = static_cast<hipStream_t>(copy_stream), es = static_cast<hipStream_t>(stream);
+    const size_t chunk_bytes = key_layout(true, n, chunk).total;
+    uint8_t *stage[2] = { static_cast<uint8_t *>(d_staging), static_cast<uint8_t *>(d_staging) + chunk_bytes };
+    hipEvent_t copied[2] = { nullptr, nullptr }, consumed[2] = { nullptr, nullptr };
+    int rc = FSS_OK;
+    hipError_t err = hipSuccess;
+    for (int i = 0; i < 2 && err == hipSuccess; i++) {
+        err = hipEventCreateWithFlags(&copied[i], hipEventDisableTiming);
+        if (err == hipSuccess) err = hipEventCreateWithFlags(&consumed[i], hipEventDisableTiming);
+    }
+    const uint8_t *src = static_cast<const uint8_t *>(h_key_chunks);
+    const size_t nchunks = (batch + chunk - 1) / chunk;
+    for (size_t c = 0; c < nchunks && err == hipSuccess && rc == FSS_OK; c++) {
+        const int h = (int)(c & 1);
+        const size_t first = c * chunk, len = (batch - first < chunk) ? batch - first : chunk;
+        const size_t bytes = key_layout(true, n, len).total;
+        if (c >= 2) err = hipStreamWaitEvent(cs, consumed[h], 0);          // the half is free again
+        if (err == hipSuccess) err = hipMemcpyAsync(stage[h], src, bytes, hipMemcpyHostToDevice, cs);
+        if (err == hipSuccess) err = hipEventRecord(copied[h], cs);
+        if (err == hipSuccess) err = hipStreamWaitEvent(es, copied[h], 0);
+        if (err != hipSuccess) break;
+        rc = eval_common(true, kPlain, party, n, len, stage[h], d_x + first, nullptr, d_out + first, nullptr, nullptr, nullptr,
+                         nullptr, stream);
+        if (rc == FSS_OK) err = hipEventRecord(consumed[h], es);
+        src += bytes;
+    }
+    // the staging halves and the events must outlive the enqueued work
+    hipError_t e2 = hipStreamSynchronize(cs);
+    hipError_t e3 = hipStreamSynchronize(es);
+    for (int i = 0; i < 2; i++) {
+        if (copied[i]) (void)hipEventDestroy(copied[i]);
+        if (consumed[i]) (void)hipEventDestroy(consumed[i]);
+    }
+    if (err == hipSuccess) err = e2 != hipSuccess ? e2 : e3;
+    if (err != hipSuccess) { g_last_hip_error = (int)err; return FSS_ELAUNCH; }
+    return rc;
+}
+
 const char *fss_strerror(int code)
 {
     switch (code) {
