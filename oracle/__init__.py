@@ -71,6 +71,16 @@ def load(path: str) -> C.CDLL:
     L.oracle_relu_open.restype = C.c_int
     L.oracle_relu_finish.argtypes = [C.c_int, C.c_int, C.c_size_t, u32p, u32p, u32p, u32p, u32p, u32p, u32p, u32p]
     L.oracle_relu_finish.restype = C.c_int
+    L.oracle_eq_mask.argtypes = [C.c_int, C.c_size_t, vp, u32p, u32p]
+    L.oracle_eq_masked_eval.argtypes = [C.c_int, C.c_int, C.c_size_t, vp, u32p, u32p, u32p]
+    L.oracle_argmax_diff_mask.argtypes = [C.c_int, C.c_size_t, C.c_int, vp, u32p, u32p]
+    L.oracle_argmax_count_mask.argtypes = [C.c_int, C.c_int, C.c_size_t, C.c_int, u32p, vp, u32p]
+    L.oracle_maxpool_unroll.argtypes = [C.c_size_t, C.c_int, C.c_int, C.c_int, C.c_int, u32p, u32p]
+    L.oracle_mul_open.argtypes = [C.c_int, C.c_size_t, u32p, u32p, u32p, u32p, u32p, u32p]
+    L.oracle_dot_finish.argtypes = [C.c_int, C.c_int, C.c_size_t, C.c_int, u32p, u32p, u32p, u32p, u32p, u32p, u32p, u32p]
+    for _name in ("oracle_eq_mask", "oracle_eq_masked_eval", "oracle_argmax_diff_mask", "oracle_argmax_count_mask",
+                  "oracle_maxpool_unroll", "oracle_mul_open", "oracle_dot_finish"):
+        getattr(L, _name).restype = C.c_int
     L.oracle_set_threads.argtypes = [C.c_int]
     L.oracle_set_threads.restype = C.c_int
     L.oracle_init()
@@ -218,6 +228,63 @@ def relu_finish(party: int, n: int, delta0, delta1, eps0, eps1, tri_a, tri_b, tr
     rc = lib().oracle_relu_finish(party, n, batch, *[_p(a, C.c_uint32) for a in arrs], _p(out, C.c_uint32))
     if rc != 0:
         raise ValueError(f"oracle relu_finish failed: {rc}")
+    return out
+
+
+def _call(name, *args):
+    rc = getattr(lib(), name)(*args)
+    if rc != 0:
+        raise ValueError(f"{name} failed: {rc}")
+
+
+def eq_mask(n: int, key: np.ndarray, y_share) -> np.ndarray:
+    y_share = _u32(y_share)
+    out = np.zeros(y_share.shape[0], dtype=np.uint32)
+    _call("oracle_eq_mask", n, y_share.shape[0], key.ctypes.data, _p(y_share, C.c_uint32), _p(out, C.c_uint32))
+    return out
+
+
+def eq_masked_eval(party: int, n: int, key: np.ndarray, masked0, masked1) -> np.ndarray:
+    m0, m1 = _u32(masked0), _u32(masked1)
+    out = np.zeros(m0.shape[0], dtype=np.uint32)
+    _call("oracle_eq_masked_eval", party, n, m0.shape[0], key.ctypes.data, _p(m0, C.c_uint32), _p(m1, C.c_uint32), _p(out, C.c_uint32))
+    return out
+
+
+def argmax_diff_mask(n: int, rows: int, m: int, cmp_key: np.ndarray, x_share) -> np.ndarray:
+    x_share = _u32(x_share).reshape(rows, m)
+    out = np.zeros(rows * m * (m - 1), dtype=np.uint32)
+    _call("oracle_argmax_diff_mask", n, rows, m, cmp_key.ctypes.data, _p(x_share, C.c_uint32), _p(out, C.c_uint32))
+    return out
+
+
+def argmax_count_mask(party: int, n: int, rows: int, m: int, w_share, eq_key: np.ndarray) -> np.ndarray:
+    w_share = _u32(w_share)
+    out = np.zeros(rows * m, dtype=np.uint32)
+    _call("oracle_argmax_count_mask", party, n, rows, m, _p(w_share, C.c_uint32), eq_key.ctypes.data, _p(out, C.c_uint32))
+    return out
+
+
+def maxpool_unroll(channels: int, h: int, w: int, k: int, s: int, x_share) -> np.ndarray:
+    x_share = _u32(x_share).reshape(channels, h, w)
+    oh, ow = (h - k) // s + 1, (w - k) // s + 1
+    out = np.zeros((channels * oh * ow, k * k), dtype=np.uint32)
+    _call("oracle_maxpool_unroll", channels, h, w, k, s, _p(x_share, C.c_uint32), _p(out, C.c_uint32))
+    return out
+
+
+def mul_open(n: int, u_share, v_share, tri_a, tri_b):
+    arrs = [_u32(a).reshape(-1) for a in (u_share, v_share, tri_a, tri_b)]
+    delta = np.zeros(arrs[0].shape[0], dtype=np.uint32)
+    eps = np.zeros_like(delta)
+    _call("oracle_mul_open", n, arrs[0].shape[0], *[_p(a, C.c_uint32) for a in arrs], _p(delta, C.c_uint32), _p(eps, C.c_uint32))
+    return delta, eps
+
+
+def dot_finish(party: int, n: int, rows: int, m: int, delta0, delta1, eps0, eps1, tri_a, tri_b, tri_c) -> np.ndarray:
+    arrs = [_u32(a).reshape(-1) for a in (delta0, delta1, eps0, eps1, tri_a, tri_b, tri_c)]
+    out = np.zeros(rows, dtype=np.uint32)
+    _call("oracle_dot_finish", party, n, rows, m, *[_p(a, C.c_uint32) for a in arrs], _p(out, C.c_uint32))
     return out
 
 

@@ -21,7 +21,8 @@
  * affine map, no lookup tables typed in, no intrinsics).
  *
  * Also here, around the comparison: the Sign protocol (Algorithm 5) and ReLU as comparison
- * plus one pointwise product with a multiplication triple (section 4.2).
+ * plus one pointwise product with a multiplication triple (section 4.2); Argmax (Algorithm 6)
+ * and MaxPool (Algorithm 7) as compositions of comparison, equality and products.
  *
  * Pins (tests/test_oracle_*.py): FIPS-197 known answers and the OpenSSL command-line tool
  * for AES; the correctness definition Eval_0 + Eval_1 = f(x) mod 2^n for EVERY x at n = 8
@@ -660,6 +661,144 @@ int oracle_relu_finish(int party, int n, size_t batch, const uint32_t *delta0, c
         uint32_t z = delta * tri_b[e] + eps * tri_a[e] + tri_c[e];
         if (party == 0) z += delta * eps;
         out[e] = z & mask;
+    }
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* Argmax (Algorithm 6) and MaxPool (Algorithm 7) as compositions of the two primitives   */
+/* ------------------------------------------------------------------------------------ */
+
+/* Equality on shared inputs, the wrapper lines of Algorithm 2: publish [[alpha]]_j + [[y]]_j,
+ * reveal x = alpha + y, evaluate; the result is a share of 1{y = 0}. */
+int oracle_eq_mask(int n, size_t batch, const void *key, const uint32_t *y_share, uint32_t *masked)
+{
+    if (bad_n(n)) return ORACLE_EINVAL;
+    if (batch == 0) return ORACLE_OK;
+    if (!key || !y_share || !masked) return ORACLE_EINVAL;
+    key_view_t k;
+    view_eq(&k, (void *)key, n, batch);
+    const uint32_t mask = ring_mask(n);
+    for (size_t e = 0; e < batch; e++)
+        masked[e] = (y_share[e] + le32(k.alpha_share + 4 * e)) & mask;
+    return ORACLE_OK;
+}
+
+int oracle_eq_masked_eval(int party, int n, size_t batch, const void *key, const uint32_t *masked0,
+                          const uint32_t *masked1, uint32_t *out)
+{
+    if (bad_n(n) || (party != 0 && party != 1)) return ORACLE_EINVAL;
+    if (batch == 0) return ORACLE_OK;
+    if (!key || !masked0 || !masked1 || !out) return ORACLE_EINVAL;
+    oracle_init();
+    key_view_t k;
+    view_eq(&k, (void *)key, n, batch);
+    const uint32_t mask = ring_mask(n);
+    long long b = (long long)batch;
+#pragma omp parallel for schedule(static)
+    for (long long e = 0; e < b; e++)
+        out[e] = eval_one(0, party, n, &k, (size_t)e, (masked0[e] + masked1[e]) & mask, NULL);
+    return ORACLE_OK;
+}
+
+/* Algorithm 6, first loop, the part before the reveal: for every vector r (of length m) and
+ * every ordered pair (j, i), i != j, the masked share of x_i - x_j under the comparison key
+ * of that pair.  Pair order: element ((r m + j)(m-1) + t) holds i = t for t < j, i = t+1 else. */
+int oracle_argmax_diff_mask(int n, size_t rows, int m, const void *cmp_key, const uint32_t *x_share, uint32_t *masked)
+{
+    if (bad_n(n) || m < 2) return ORACLE_EINVAL;
+    if (rows == 0) return ORACLE_OK;
+    if (!cmp_key || !x_share || !masked) return ORACLE_EINVAL;
+    const size_t batch = rows * (size_t)m * (size_t)(m - 1);
+    key_view_t k;
+    view_cmp(&k, (void *)cmp_key, n, batch);
+    const uint32_t mask = ring_mask(n);
+    for (size_t r = 0; r < rows; r++)
+        for (int j = 0; j < m; j++)
+            for (int t = 0; t < m - 1; t++) {
+                const int i = t < j ? t : t + 1;
+                const size_t e = (r * (size_t)m + (size_t)j) * (size_t)(m - 1) + (size_t)t;
+                const uint32_t y = x_share[r * (size_t)m + (size_t)i] - x_share[r * (size_t)m + (size_t)j];
+                masked[e] = (y + le32(k.alpha_share + 4 * e)) & mask;
+            }
+    return ORACLE_OK;
+}
+
+/* Algorithm 6, between the loops: [[s_j]] = sum over i != j of the comparison shares, then the
+ * masked share of s_j - (m - 1) under the equality key of (r, j) (the constant is subtracted by
+ * party 0). */
+int oracle_argmax_count_mask(int party, int n, size_t rows, int m, const uint32_t *w_share, const void *eq_key,
+                             uint32_t *masked)
+{
+    if (bad_n(n) || m < 2 || (party != 0 && party != 1)) return ORACLE_EINVAL;
+    if (rows == 0) return ORACLE_OK;
+    if (!w_share || !eq_key || !masked) return ORACLE_EINVAL;
+    const size_t batch = rows * (size_t)m;
+    key_view_t k;
+    view_eq(&k, (void *)eq_key, n, batch);
+    const uint32_t mask = ring_mask(n);
+    for (size_t e = 0; e < batch; e++) {
+        uint32_t sum = 0;
+        for (int t = 0; t < m - 1; t++) sum += w_share[e * (size_t)(m - 1) + (size_t)t];
+        if (party == 0) sum -= (uint32_t)(m - 1);
+        masked[e] = (sum + le32(k.alpha_share + 4 * e)) & mask;
+    }
+    return ORACLE_OK;
+}
+
+/* Algorithm 7, the unrolling: windows of k x k, stride s, no padding, of a [channels][h][w]
+ * tensor of shares; one row of k^2 values per window, windows in (channel, row, column) order. */
+int oracle_maxpool_unroll(size_t channels, int h, int w, int k, int s, const uint32_t *x_share, uint32_t *rows)
+{
+    if (k < 1 || s < 1 || h < k || w < k) return ORACLE_EINVAL;
+    if (channels == 0) return ORACLE_OK;
+    if (!x_share || !rows) return ORACLE_EINVAL;
+    const int oh = (h - k) / s + 1, ow = (w - k) / s + 1;
+    size_t out = 0;
+    for (size_t c = 0; c < channels; c++)
+        for (int oy = 0; oy < oh; oy++)
+            for (int ox = 0; ox < ow; ox++)
+                for (int dy = 0; dy < k; dy++)
+                    for (int dx = 0; dx < k; dx++)
+                        rows[out++] = x_share[(c * (size_t)h + (size_t)(oy * s + dy)) * (size_t)w + (size_t)(ox * s + dx)];
+    return ORACLE_OK;
+}
+
+/* Pointwise product with multiplication triples (section 4.2, MatMul paragraph): the messages
+ * delta_j = [[u]]_j - [[a]]_j, eps_j = [[v]]_j - [[b]]_j ... */
+int oracle_mul_open(int n, size_t count, const uint32_t *u_share, const uint32_t *v_share, const uint32_t *tri_a,
+                    const uint32_t *tri_b, uint32_t *delta, uint32_t *eps)
+{
+    if (bad_n(n)) return ORACLE_EINVAL;
+    if (count == 0) return ORACLE_OK;
+    if (!u_share || !v_share || !tri_a || !tri_b || !delta || !eps) return ORACLE_EINVAL;
+    const uint32_t mask = ring_mask(n);
+    for (size_t e = 0; e < count; e++) {
+        delta[e] = (u_share[e] - tri_a[e]) & mask;
+        eps[e] = (v_share[e] - tri_b[e]) & mask;
+    }
+    return ORACLE_OK;
+}
+
+/* ... and the inner product of Algorithm 7: [[y_r]]_j = sum over the m entries of row r of
+ * delta.[[b]]_j + eps.[[a]]_j + [[c]]_j (+ delta.eps for party 0). */
+int oracle_dot_finish(int party, int n, size_t rows, int m, const uint32_t *delta0, const uint32_t *delta1,
+                      const uint32_t *eps0, const uint32_t *eps1, const uint32_t *tri_a, const uint32_t *tri_b,
+                      const uint32_t *tri_c, uint32_t *out)
+{
+    if (bad_n(n) || m < 1 || (party != 0 && party != 1)) return ORACLE_EINVAL;
+    if (rows == 0) return ORACLE_OK;
+    if (!delta0 || !delta1 || !eps0 || !eps1 || !tri_a || !tri_b || !tri_c || !out) return ORACLE_EINVAL;
+    const uint32_t mask = ring_mask(n);
+    for (size_t r = 0; r < rows; r++) {
+        uint32_t acc = 0;
+        for (int i = 0; i < m; i++) {
+            const size_t e = r * (size_t)m + (size_t)i;
+            const uint32_t delta = delta0[e] + delta1[e], eps = eps0[e] + eps1[e];
+            acc += delta * tri_b[e] + eps * tri_a[e] + tri_c[e];
+            if (party == 0) acc += delta * eps;
+        }
+        out[r] = acc & mask;
     }
     return ORACLE_OK;
 }

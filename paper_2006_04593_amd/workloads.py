@@ -142,6 +142,21 @@ def relu_inputs(rng: np.random.Generator, n: int, y: np.ndarray) -> ReluInputs:
                       tri_a=additive_shares(rng, n, a), tri_b=additive_shares(rng, n, b), tri_c=additive_shares(rng, n, c))
 
 
+@dataclass
+class TripleShares:
+    """Additive shares of `count` multiplication triples (dealer material): c = a * b mod 2^n."""
+    a: tuple
+    b: tuple
+    c: tuple
+
+
+def triple_shares(rng: np.random.Generator, n: int, count: int) -> TripleShares:
+    m = np.uint64(ring_mask(n))
+    a = uniform_ring(rng, n, count).astype(np.uint64)
+    b = uniform_ring(rng, n, count).astype(np.uint64)
+    return TripleShares(a=additive_shares(rng, n, a), b=additive_shares(rng, n, b), c=additive_shares(rng, n, (a * b) & m))
+
+
 def maxpool_taps(seed: int, channels: int = 64, hw: int = 112) -> np.ndarray:
     """[9, C*(hw/2)*(hw/2)] int64: the nine taps of every 3x3 stride-2 pad-1 window."""
     rng = np.random.default_rng(seed)

@@ -46,6 +46,13 @@ MUTANTS = [
     ("relu_eps_sign", "eps[e] = (v - tri_b[e]) & mask;", "eps[e] = (v + tri_b[e]) & mask;", "relu"),
     ("relu_triple_operands_swapped", "uint32_t z = delta * tri_b[e] + eps * tri_a[e] + tri_c[e];",
      "uint32_t z = delta * tri_a[e] + eps * tri_b[e] + tri_c[e];", "relu"),
+    ("argmax_pair_index_off", "const int i = t < j ? t : t + 1;", "const int i = t;", "argmax"),
+    ("argmax_difference_reversed", "const uint32_t y = x_share[r * (size_t)m + (size_t)i] - x_share[r * (size_t)m + (size_t)j];",
+     "const uint32_t y = x_share[r * (size_t)m + (size_t)j] - x_share[r * (size_t)m + (size_t)i];", "argmax"),
+    ("argmax_count_constant", "if (party == 0) sum -= (uint32_t)(m - 1);", "if (party == 0) sum -= (uint32_t)m;", "argmax"),
+    ("dot_public_product_dropped", "if (party == 0) acc += delta * eps;", "", "argmax"),
+    ("unroll_stride_ignored", "rows[out++] = x_share[(c * (size_t)h + (size_t)(oy * s + dy)) * (size_t)w + (size_t)(ox * s + dx)];",
+     "rows[out++] = x_share[(c * (size_t)h + (size_t)(oy + dy)) * (size_t)w + (size_t)(ox + dx)];", "argmax"),
     ("sign_mask_subtracts", "masked[e] = (y_share[e] + le32(k.alpha_share + 4 * e)) & mask;",
      "masked[e] = (y_share[e] - le32(k.alpha_share + 4 * e)) & mask;", "relu"),
 ]
@@ -105,7 +112,27 @@ def relu_identity_holds(n=8):
     return np.array_equal((z[0] + z[1]) & np.uint32(mask), ((y.astype(np.uint64) * (1 - le)) & mask).astype(np.uint32))
 
 
+def maxpool_holds():
+    import argmax_flow as F
+    n, channels, h, w, k = 32, 2, 6, 8, 2
+    rng = np.random.default_rng(99)
+    x = W.fixed_point_normal(rng, (channels, h, w))
+    x[0, 0, 0] = x[0, 0, 1] = x[0, :2, :2].max() + 5          # a tie inside the first window
+    oh, ow = (h - k) // 2 + 1, (w - k) // 2 + 1
+    rows, m = channels * oh * ow, k * k
+    mat = F.material(rng, n, rows, m)
+    s0, s1 = W.additive_shares(rng, n, x.reshape(-1).astype(np.int64).astype(np.uint64))
+    t = F.maxpool(F.OracleBackend(), mat, channels, h, w, k, (s0.reshape(x.shape), s1.reshape(x.shape)))
+    win = np.stack([x[c, 2 * i:2 * i + k, 2 * j:2 * j + k].reshape(-1) for c in range(channels) for i in range(oh) for j in range(ow)])
+    onehot = (t["onehot"][0] + t["onehot"][1]).reshape(rows, m)
+    out = t["out"][0] + t["out"][1]
+    want_hot = (win == win.max(axis=1, keepdims=True)).astype(np.uint32)
+    want = ((win * want_hot).sum(axis=1) & 0xFFFFFFFF).astype(np.uint32)
+    return np.array_equal(onehot, want_hot) and np.array_equal(out, want)
+
+
 def test_unmodified_oracle_passes_the_compact_pins():
+    assert maxpool_holds()
     assert reconstruction_holds("cmp") and reconstruction_holds("eq")
     assert aes_known_answer_holds() and prg_definition_holds()
     assert relu_identity_holds()
@@ -118,6 +145,8 @@ def test_planted_mistake_is_caught(tmp_path, monkeypatch, name, old, new, pin):
         assert not aes_known_answer_holds()
     elif pin == "prg":
         assert aes_known_answer_holds() and not prg_definition_holds()
+    elif pin == "argmax":
+        assert reconstruction_holds("cmp") and not maxpool_holds()
     elif pin == "relu":
         assert reconstruction_holds("cmp") and not relu_identity_holds()
     elif pin == "cmp":
