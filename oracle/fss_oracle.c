@@ -680,7 +680,7 @@ int oracle_eq_mask(int n, size_t batch, const void *key, const uint32_t *y_share
     view_eq(&k, (void *)key, n, batch);
     const uint32_t mask = ring_mask(n);
     for (size_t e = 0; e < batch; e++)
-        masked[e] = (y_share[e] + le32(k.alpha_share + 4 * e)) & mask;
+        masked[e] = (le32(k.alpha_share + 4 * e) + y_share[e]) & mask;
     return ORACLE_OK;
 }
 
