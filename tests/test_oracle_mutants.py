@@ -53,8 +53,8 @@ MUTANTS = [
     ("dot_public_product_dropped", "if (party == 0) acc += delta * eps;", "", "argmax"),
     ("unroll_stride_ignored", "rows[out++] = x_share[(c * (size_t)h + (size_t)(oy * s + dy)) * (size_t)w + (size_t)(ox * s + dx)];",
      "rows[out++] = x_share[(c * (size_t)h + (size_t)(oy + dy)) * (size_t)w + (size_t)(ox + dx)];", "argmax"),
-    ("eq_mask_subtracts", "masked[e] = (le32(k.alpha_share + 4 * e) + y_share[e]) & mask;",
-     "masked[e] = (le32(k.alpha_share + 4 * e) - y_share[e]) & mask;", "argmax"),
+    ("eq_mask_drops_alpha", "masked[e] = (le32(k.alpha_share + 4 * e) + y_share[e]) & mask;",
+     "masked[e] = y_share[e] & mask;", "argmax"),
     ("sign_mask_subtracts", "masked[e] = (y_share[e] + le32(k.alpha_share + 4 * e)) & mask;",
      "masked[e] = (y_share[e] - le32(k.alpha_share + 4 * e)) & mask;", "relu"),
 ]
