@@ -80,3 +80,19 @@ def test_maxpool_equals_plain_maxpool(k, h):
     good = unique & (onehot.sum(axis=1) == 1)
     assert good.mean() > 0.9
     assert np.array_equal(out[good], (win.max(axis=1)[good] & 0xFFFFFFFF).astype(np.uint32))
+
+
+@pytest.mark.parametrize("n", [5, 8, 32])
+def test_equality_on_shared_inputs(n):
+    """The wrapper lines of Algorithm 2: publish [[alpha]] + [[y]], reveal, evaluate -> 1{y = 0}."""
+    import oracle
+    rng = np.random.default_rng(40 + n)
+    size = 1 << min(n, 10)
+    y = np.arange(size, dtype=np.uint64) if n <= 10 else np.where(rng.random(size) < 0.3, 0, W.uniform_ring(rng, n, size)).astype(np.uint64)
+    g = W.gen_inputs(rng, n, size)
+    ys = W.additive_shares(rng, n, y)
+    k = oracle.gen("eq", n, g.alpha, g.r, g.seed0, g.seed1)
+    m = [oracle.eq_mask(n, k[j], ys[j]) for j in (0, 1)]
+    assert np.array_equal(rec(m, n), ((y + g.alpha) & W.ring_mask(n)).astype(np.uint32))
+    o = [oracle.eq_masked_eval(j, n, k[j], m[0], m[1]) for j in (0, 1)]
+    assert np.array_equal(rec(o, n), (y == 0).astype(np.uint32))

@@ -54,7 +54,7 @@ MUTANTS = [
     ("unroll_stride_ignored", "rows[out++] = x_share[(c * (size_t)h + (size_t)(oy * s + dy)) * (size_t)w + (size_t)(ox * s + dx)];",
      "rows[out++] = x_share[(c * (size_t)h + (size_t)(oy + dy)) * (size_t)w + (size_t)(ox + dx)];", "argmax"),
     ("eq_mask_drops_alpha", "masked[e] = (le32(k.alpha_share + 4 * e) + y_share[e]) & mask;",
-     "masked[e] = y_share[e] & mask;", "argmax"),
+     "masked[e] = y_share[e] & mask;", "eqshared"),
     ("sign_mask_subtracts", "masked[e] = (y_share[e] + le32(k.alpha_share + 4 * e)) & mask;",
      "masked[e] = (y_share[e] - le32(k.alpha_share + 4 * e)) & mask;", "relu"),
 ]
@@ -133,8 +133,21 @@ def maxpool_holds():
     return np.array_equal(onehot, want_hot) and np.array_equal(out, want)
 
 
+def shared_equality_holds(n=8):
+    """Algorithm 2 with its wrapper lines: shares of y in, shares of 1{y = 0} out, for every y."""
+    size = 1 << n
+    y = np.arange(size, dtype=np.uint64)
+    rng = np.random.default_rng(808)
+    g = W.gen_inputs(rng, n, size)
+    ys = W.additive_shares(rng, n, y)
+    k = oracle.gen("eq", n, g.alpha, g.r, g.seed0, g.seed1)
+    m = [oracle.eq_mask(n, k[j], ys[j]) for j in (0, 1)]
+    o = [oracle.eq_masked_eval(j, n, k[j], m[0], m[1]) for j in (0, 1)]
+    return np.array_equal((o[0] + o[1]) & np.uint32(W.ring_mask(n)), (y == 0).astype(np.uint32))
+
+
 def test_unmodified_oracle_passes_the_compact_pins():
-    assert maxpool_holds()
+    assert maxpool_holds() and shared_equality_holds()
     assert reconstruction_holds("cmp") and reconstruction_holds("eq")
     assert aes_known_answer_holds() and prg_definition_holds()
     assert relu_identity_holds()
@@ -147,6 +160,8 @@ def test_planted_mistake_is_caught(tmp_path, monkeypatch, name, old, new, pin):
         assert not aes_known_answer_holds()
     elif pin == "prg":
         assert aes_known_answer_holds() and not prg_definition_holds()
+    elif pin == "eqshared":
+        assert reconstruction_holds("eq") and not shared_equality_holds()
     elif pin == "argmax":
         assert reconstruction_holds("cmp") and not maxpool_holds()
     elif pin == "relu":
