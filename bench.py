@@ -134,6 +134,100 @@ def relu_layer_bench(args, dev):
     }
 
 
+def maxpool_layer_bench(args, dev):
+    """The paper's MaxPool (Algorithm 7: unroll, Argmax per window with k^2(k^2-1) comparisons and
+    k^2 equalities, inner product), 3x3 windows, stride 2, no padding, over 64 x 112 x 112 shared
+    activations: 193,600 windows, 13.9 M comparisons and 1.7 M equalities per party.  A step is
+    every online kernel of BOTH parties; keys and triples are dealer material made beforehand."""
+    import numpy as np
+    import torch
+
+    import paper_2006_04593_amd as fss
+    from paper_2006_04593_amd import workloads as W
+
+    n, C, H, Wd, k = N_BITS, 64, 112, 112, 3
+    oh, ow = (H - k) // 2 + 1, (Wd - k) // 2 + 1
+    rows, m = C * oh * ow, k * k
+    ncmp, neq = rows * m * (m - 1), rows * m
+    rng = np.random.default_rng(W.BASE_SEED + 4)
+    x = W.fixed_point_normal(rng, (C, H, Wd))
+    xs = W.additive_shares(rng, n, x.reshape(-1).astype(np.int64).astype(np.uint64))
+    tr = W.triple_shares(rng, n, neq)
+
+    def T(a):
+        return torch.from_numpy(a.view(np.int32) if a.dtype == np.uint32 else a).to(dev)
+
+    def keys(kind, count):
+        g = W.gen_inputs(rng, n, count)
+        nb = (fss.cmp_key_bytes if kind == "cmp" else fss.eq_key_bytes)(n, count)
+        kk = [torch.empty(nb, dtype=torch.uint8, device=dev) for _ in range(2)]
+        (fss.cmp_gen if kind == "cmp" else fss.eq_gen)(n, count, T(g.alpha), T(g.r), T(g.seed0), T(g.seed1), kk[0], kk[1])
+        torch.cuda.synchronize()
+        return kk
+
+    kc, ke = keys("cmp", ncmp), keys("eq", neq)
+    xd = [T(v) for v in xs]
+    ta, tb, tc = ([T(p[j]) for j in (0, 1)] for p in (tr.a, tr.b, tr.c))
+    buf = lambda cnt: [torch.empty(cnt, dtype=torch.int32, device=dev) for _ in range(2)]
+    unrolled, mc, w, me, hot, dl, ep, out = buf(neq), buf(ncmp), buf(ncmp), buf(neq), buf(neq), buf(neq), buf(neq), buf(rows)
+    stream = torch.cuda.current_stream()
+    marks = []
+
+    def step(timed):
+        ev = lambda: torch.cuda.Event(enable_timing=True)
+        for j in (0, 1):
+            fss.maxpool_unroll(C, H, Wd, k, 2, xd[j], unrolled[j], stream=stream)
+            fss.argmax_diff_mask(n, rows, m, kc[j], unrolled[j], mc[j], stream=stream)
+        for j in (0, 1):
+            e = [ev(), ev(), ev(), ev()] if timed else None
+            if timed:
+                e[0].record(stream)
+            fss.sign_eval(j, n, ncmp, kc[j], mc[0], mc[1], w[j], stream=stream)
+            if timed:
+                e[1].record(stream)
+            fss.argmax_count_mask(j, n, rows, m, w[j], ke[j], me[j], stream=stream)
+            if timed:
+                marks.append(e)
+        for j in (0, 1):
+            if timed:
+                marks[-2 + j][2].record(stream)
+            fss.eq_masked_eval(j, n, neq, ke[j], me[0], me[1], hot[j], stream=stream)
+            if timed:
+                marks[-2 + j][3].record(stream)
+            fss.mul_open(n, neq, unrolled[j], hot[j], ta[j], tb[j], dl[j], ep[j], stream=stream)
+        for j in (0, 1):
+            fss.dot_finish(j, n, rows, m, dl[0], dl[1], ep[0], ep[1], ta[j], tb[j], tc[j], out[j], stream=stream)
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    y = (out[0] + out[1]).cpu().numpy().view(np.uint32)
+    win = np.lib.stride_tricks.sliding_window_view(x, (k, k), axis=(1, 2))[:, ::2, ::2].reshape(rows, m)
+    agree = (y == (win.max(axis=1) & 0xFFFFFFFF).astype(np.uint32)).mean()
+    assert agree > 0.99, f"max-pool agreement {agree}"       # ties and Sign wrap-arounds aside
+    cmp_ms = sum(e[0].elapsed_time(e[1]) for e in marks) / len(marks)
+    eq_ms = sum(e[2].elapsed_time(e[3]) for e in marks) / len(marks)
+    lds_gbs = ncmp * LDS_BYTES_PER_EVAL / (cmp_ms * 1e-3) / 1e9
+    return {
+        "metric": "shared MaxPool windows/sec per party (3x3 stride 2, n=32, lambda=128)",
+        "value": rows / ((wall / args.steps) / 2), "unit": "windows/s/party", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u32", "data": "synthetic",
+        "config": {"workload": "MaxPool 3x3 stride 2 (no padding) over 64x112x112 shared activations, Algorithm 7: "
+                               f"{rows} windows, {ncmp} comparisons + {neq} equalities + {neq} products per party",
+                   "n": n, "lambda": 128},
+        "cmp_eval_ms": cmp_ms, "cmp_evals_per_s": ncmp / (cmp_ms * 1e-3), "eq_eval_ms": eq_ms,
+        "eq_evals_per_s": neq / (eq_ms * 1e-3), "agreement_with_plain_maxpool": agree,
+        "roofline": {"bound": "lds", "kernel": "eval_kernel<cmp, sign>", "achieved": lds_gbs, "peak": PEAK_LDS_GBS,
+                     "unit": "GB/s", "frac": lds_gbs / PEAK_LDS_GBS, "traffic": None},
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -141,9 +235,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--batch", type=int, default=1 << 22, help="elements per step (default: the 2^22 configuration)")
     ap.add_argument("--cpu-sample", type=int, default=1 << 18, help="elements for the oracle timing; 0 skips it")
-    ap.add_argument("--workload", choices=["large", "relu"], default="large",
+    ap.add_argument("--workload", choices=["large", "relu", "maxpool"], default="large",
                     help="large: the headline 2^22 comparison Gen+Eval step; relu: one shared ReLU layer of "
-                         "64x112x112 activations (Sign mask, fused comparison+open round, finish) per party")
+                         "64x112x112 activations (Sign mask, fused comparison+open round, finish) per party; "
+                         "maxpool: the paper's MaxPool (Algorithm 7), 3x3 stride 2 over 64x112x112")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also launch one plain elementwise copy over 1 GiB, so that a rocprofv3 --pmc run of this "
                          "command holds the counter's reading for a kernel of known traffic")
@@ -164,6 +259,9 @@ def main():
     torch.cuda.set_device(dev)
     if args.workload == "relu":
         print(json.dumps(relu_layer_bench(args, dev)))
+        return
+    if args.workload == "maxpool":
+        print(json.dumps(maxpool_layer_bench(args, dev)))
         return
     B, n = args.batch, N_BITS
     w = W.uniform_workload("cmp", n, B, seed=W.BASE_SEED + 5, name="config5")

@@ -141,6 +141,44 @@ int fss_relu_finish(int party, int n, size_t batch, const uint32_t *d_delta0, co
                     const uint32_t *d_eps0, const uint32_t *d_eps1, const uint32_t *d_tri_a,
                     const uint32_t *d_tri_b, const uint32_t *d_tri_c, uint32_t *d_out, fss_stream_t stream);
 
+/* ---- Argmax (Algorithm 6) and MaxPool (Algorithm 7) as compositions ----------------------
+ *
+ * Equality on shared inputs (wrapper lines of Algorithm 2): fss_eq_mask publishes
+ * [[alpha]]_j + [[y]]_j from an equality key; fss_eq_masked_eval adds the two published vectors
+ * and evaluates: a share of 1{y = 0}.
+ *
+ * Argmax of `rows` vectors of m shared values, 2 rounds:
+ *   fss_argmax_diff_mask   masked shares of x_i - x_j for every ordered pair (j, i), i != j, under
+ *                          comparison keys for rows*m*(m-1) elements; element ((r m + j)(m-1) + t)
+ *                          holds i = t for t < j and i = t + 1 otherwise            -> round 1
+ *   fss_sign_eval          on the revealed differences: shares of 1{x_i <= x_j}
+ *   fss_argmax_count_mask  [[s_j]] = sum of the m-1 shares of (r, j); masked share of s_j - (m-1)
+ *                          under equality keys for rows*m elements                  -> round 2
+ *   fss_eq_masked_eval     shares of 1{s_j = m-1}: the argmax in one-hot form (all maxima on ties)
+ * MaxPool (k x k windows, stride s, no padding) of a [channels][h][w] tensor of shares, 3 rounds:
+ *   fss_maxpool_unroll     one row of k*k shares per window, windows in (channel, y, x) order
+ *   Argmax of the rows (m = k*k), then the inner product of each row with its one-hot vector:
+ *   fss_mul_open           delta_j = [[u]]_j - [[a]]_j, eps_j = [[v]]_j - [[b]]_j   -> round 3
+ *   fss_dot_finish         [[y_r]]_j = sum over the row of delta.[[b]]_j + eps.[[a]]_j + [[c]]_j
+ *                          (+ delta.eps for party 0)
+ * All arrays are u32 device arrays; sizes follow from rows, m, channels, h, w, k, s. */
+int fss_eq_mask(int n, size_t batch, const void *d_key, const uint32_t *d_y_share, uint32_t *d_masked,
+                fss_stream_t stream);
+int fss_eq_masked_eval(int party, int n, size_t batch, const void *d_key, const uint32_t *d_masked0,
+                       const uint32_t *d_masked1, uint32_t *d_out, fss_stream_t stream);
+int fss_argmax_diff_mask(int n, size_t rows, int m, const void *d_cmp_key, const uint32_t *d_x_share,
+                         uint32_t *d_masked, fss_stream_t stream);
+int fss_argmax_count_mask(int party, int n, size_t rows, int m, const uint32_t *d_w_share,
+                          const void *d_eq_key, uint32_t *d_masked, fss_stream_t stream);
+int fss_maxpool_unroll(size_t channels, int h, int w, int k, int s, const uint32_t *d_x_share,
+                       uint32_t *d_rows, fss_stream_t stream);
+int fss_mul_open(int n, size_t count, const uint32_t *d_u_share, const uint32_t *d_v_share,
+                 const uint32_t *d_tri_a, const uint32_t *d_tri_b, uint32_t *d_delta, uint32_t *d_eps,
+                 fss_stream_t stream);
+int fss_dot_finish(int party, int n, size_t rows, int m, const uint32_t *d_delta0, const uint32_t *d_delta1,
+                   const uint32_t *d_eps0, const uint32_t *d_eps1, const uint32_t *d_tri_a,
+                   const uint32_t *d_tri_b, const uint32_t *d_tri_c, uint32_t *d_out, fss_stream_t stream);
+
 /* ---- keys kept in host memory, imported during the online phase --------------------------
  *
  * The paper notes (section 5.2) that device memory for keys limits the batch size and that

@@ -5,6 +5,13 @@ include/fss.h); this package only marshals arguments.  There is no CPU fallback:
 library has not been built, importing `binding` functions raises.
 """
 from .binding import (  # noqa: F401
+    argmax_count_mask,
+    argmax_diff_mask,
+    dot_finish,
+    eq_mask,
+    eq_masked_eval,
+    maxpool_unroll,
+    mul_open,
     FssError,
     build,
     cmp_chunked_key_bytes,

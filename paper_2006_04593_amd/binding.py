@@ -14,7 +14,9 @@ _SO = os.path.join(_HERE, "libfss_mi355.so")
 _lib: Optional[C.CDLL] = None
 
 EXPORTS = ("fss_cmp_key_bytes", "fss_eq_key_bytes", "fss_cmp_gen", "fss_cmp_eval", "fss_eq_gen", "fss_eq_eval",
-           "fss_sign_mask", "fss_sign_eval", "fss_relu_open", "fss_relu_finish", "fss_cmp_chunked_key_bytes",
+           "fss_sign_mask", "fss_sign_eval", "fss_relu_open", "fss_relu_finish", "fss_eq_mask", "fss_eq_masked_eval",
+           "fss_argmax_diff_mask", "fss_argmax_count_mask", "fss_maxpool_unroll", "fss_mul_open", "fss_dot_finish",
+           "fss_cmp_chunked_key_bytes",
            "fss_cmp_eval_streamed", "fss_strerror", "fss_last_hip_error")
 
 HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
@@ -84,6 +86,16 @@ def lib() -> C.CDLL:
         L.fss_relu_open.argtypes = [i, i, sz, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.fss_relu_finish.argtypes = [i, i, sz, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         for name in ("fss_sign_mask", "fss_sign_eval", "fss_relu_open", "fss_relu_finish"):
+            getattr(L, name).restype = i
+        L.fss_eq_mask.argtypes = [i, sz, vp, vp, vp, vp]
+        L.fss_eq_masked_eval.argtypes = [i, i, sz, vp, vp, vp, vp, vp]
+        L.fss_argmax_diff_mask.argtypes = [i, sz, i, vp, vp, vp, vp]
+        L.fss_argmax_count_mask.argtypes = [i, i, sz, i, vp, vp, vp, vp]
+        L.fss_maxpool_unroll.argtypes = [sz, i, i, i, i, vp, vp, vp]
+        L.fss_mul_open.argtypes = [i, sz, vp, vp, vp, vp, vp, vp, vp]
+        L.fss_dot_finish.argtypes = [i, i, sz, i, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        for name in ("fss_eq_mask", "fss_eq_masked_eval", "fss_argmax_diff_mask", "fss_argmax_count_mask", "fss_maxpool_unroll",
+                     "fss_mul_open", "fss_dot_finish"):
             getattr(L, name).restype = i
         L.fss_cmp_chunked_key_bytes.argtypes = [i, sz, sz]
         L.fss_cmp_chunked_key_bytes.restype = sz
@@ -175,3 +187,34 @@ def cmp_eval_streamed(party: int, n: int, batch: int, chunk: int, h_key_chunks, 
     """fss_cmp_eval_streamed: h_key_chunks is a pinned HOST tensor in the chunked layout."""
     _check(lib().fss_cmp_eval_streamed(party, n, batch, chunk, _ptr(h_key_chunks), _ptr(d_x), _ptr(d_out), _ptr(d_staging),
                                        _stream(copy_stream), _stream(stream)))
+
+
+def eq_mask(n: int, batch: int, d_key, d_y_share, d_masked, stream=None) -> None:
+    _check(lib().fss_eq_mask(n, batch, _ptr(d_key), _ptr(d_y_share), _ptr(d_masked), _stream(stream)))
+
+
+def eq_masked_eval(party: int, n: int, batch: int, d_key, d_masked0, d_masked1, d_out, stream=None) -> None:
+    _check(lib().fss_eq_masked_eval(party, n, batch, _ptr(d_key), _ptr(d_masked0), _ptr(d_masked1), _ptr(d_out), _stream(stream)))
+
+
+def argmax_diff_mask(n: int, rows: int, m: int, d_cmp_key, d_x_share, d_masked, stream=None) -> None:
+    _check(lib().fss_argmax_diff_mask(n, rows, m, _ptr(d_cmp_key), _ptr(d_x_share), _ptr(d_masked), _stream(stream)))
+
+
+def argmax_count_mask(party: int, n: int, rows: int, m: int, d_w_share, d_eq_key, d_masked, stream=None) -> None:
+    _check(lib().fss_argmax_count_mask(party, n, rows, m, _ptr(d_w_share), _ptr(d_eq_key), _ptr(d_masked), _stream(stream)))
+
+
+def maxpool_unroll(channels: int, h: int, w: int, k: int, s: int, d_x_share, d_rows, stream=None) -> None:
+    _check(lib().fss_maxpool_unroll(channels, h, w, k, s, _ptr(d_x_share), _ptr(d_rows), _stream(stream)))
+
+
+def mul_open(n: int, count: int, d_u_share, d_v_share, d_tri_a, d_tri_b, d_delta, d_eps, stream=None) -> None:
+    _check(lib().fss_mul_open(n, count, _ptr(d_u_share), _ptr(d_v_share), _ptr(d_tri_a), _ptr(d_tri_b), _ptr(d_delta), _ptr(d_eps),
+                              _stream(stream)))
+
+
+def dot_finish(party: int, n: int, rows: int, m: int, d_delta0, d_delta1, d_eps0, d_eps1, d_tri_a, d_tri_b, d_tri_c, d_out,
+               stream=None) -> None:
+    _check(lib().fss_dot_finish(party, n, rows, m, _ptr(d_delta0), _ptr(d_delta1), _ptr(d_eps0), _ptr(d_eps1), _ptr(d_tri_a),
+                                _ptr(d_tri_b), _ptr(d_tri_c), _ptr(d_out), _stream(stream)))

@@ -161,6 +161,81 @@ __global__ void sign_mask_kernel(const uint32_t *alpha_share, const uint32_t *y_
         masked[e] = (y_share[e] + alpha_share[e]) & mask;
 }
 
+// Algorithm 6, first loop before the reveal: masked share of x_i - x_j for every ordered pair
+// (j, i), i != j, of every row.  e = (r m + j)(m - 1) + t with i = t for t < j, else t + 1.
+__global__ void argmax_diff_mask_kernel(const uint32_t *alpha_share, const uint32_t *x_share, uint32_t *masked, size_t rows,
+                                        uint32_t m, uint32_t mask)
+{
+    const size_t total = rows * m * (m - 1);
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += stride) {
+        const size_t rj = e / (m - 1);
+        const uint32_t t = (uint32_t)(e - rj * (m - 1));
+        const size_t r = rj / m;
+        const uint32_t j = (uint32_t)(rj - r * m);
+        const uint32_t i = t < j ? t : t + 1;
+        masked[e] = (x_share[r * m + i] - x_share[r * m + j] + alpha_share[e]) & mask;
+    }
+}
+
+// Algorithm 6 between the loops: [[s_j]] = sum of the m - 1 comparison shares of (r, j), then the
+// masked share of s_j - (m - 1) under the equality key of (r, j)
+__global__ void argmax_count_mask_kernel(const uint32_t *alpha_share, const uint32_t *w_share, uint32_t *masked, size_t count,
+                                         uint32_t m, uint32_t mask, int party)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < count; e += stride) {
+        uint32_t sum = party == 0 ? 0u - (m - 1) : 0u;
+        for (uint32_t t = 0; t < m - 1; t++) sum += w_share[e * (m - 1) + t];
+        masked[e] = (sum + alpha_share[e]) & mask;
+    }
+}
+
+// Algorithm 7, unrolling: one row of k*k shares per k x k window (stride s, no padding)
+__global__ void maxpool_unroll_kernel(const uint32_t *x_share, uint32_t *rows_out, size_t channels, int h, int w, int k, int s,
+                                      int oh, int ow)
+{
+    const size_t total = channels * (size_t)oh * ow * k * k;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += stride) {
+        size_t q = e;
+        const int dx = (int)(q % k); q /= k;
+        const int dy = (int)(q % k); q /= k;
+        const int ox = (int)(q % ow); q /= ow;
+        const int oy = (int)(q % oh); q /= oh;
+        rows_out[e] = x_share[(q * h + (size_t)(oy * s + dy)) * w + (size_t)(ox * s + dx)];
+    }
+}
+
+// messages of a pointwise product with multiplication triples (section 4.2)
+__global__ void mul_open_kernel(const uint32_t *u, const uint32_t *v, const uint32_t *ta, const uint32_t *tb, uint32_t *delta,
+                                uint32_t *eps, size_t count, uint32_t mask)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < count; e += stride) {
+        delta[e] = (u[e] - ta[e]) & mask;
+        eps[e] = (v[e] - tb[e]) & mask;
+    }
+}
+
+// inner product of Algorithm 7: one output per row of m products
+__global__ void dot_finish_kernel(const uint32_t *d0, const uint32_t *d1, const uint32_t *e0, const uint32_t *e1,
+                                  const uint32_t *ta, const uint32_t *tb, const uint32_t *tc, uint32_t *out, size_t rows,
+                                  uint32_t m, uint32_t mask, int party)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t r = (size_t)blockIdx.x * blockDim.x + threadIdx.x; r < rows; r += stride) {
+        uint32_t acc = 0;
+        for (uint32_t i = 0; i < m; i++) {
+            const size_t e = r * m + i;
+            const uint32_t delta = d0[e] + d1[e], eps = e0[e] + e1[e];
+            acc += delta * tb[e] + eps * ta[e] + tc[e];
+            if (party == 0) acc += delta * eps;
+        }
+        out[r] = acc & mask;
+    }
+}
+
 // [[u.v]]_j = delta.[[b]]_j + eps.[[a]]_j + [[c]]_j (+ delta.eps for party 0), section 4.2
 __global__ void relu_finish_kernel(const uint32_t *d0, const uint32_t *d1, const uint32_t *e0, const uint32_t *e1,
                                    const uint32_t *ta, const uint32_t *tb, const uint32_t *tc, uint32_t *out,
@@ -350,10 +425,11 @@ static int prepare_device(DeviceInfo *info)
         if (err == hipSuccess) err = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (err != hipSuccess) { g_last_hip_error = (int)err; return FSS_ELAUNCH; }
         if ((uint32_t)lds < kLdsBytes) { cache[dev].ok = -1; g_last_hip_error = 0; return FSS_EDEVICE; }
-        const void *fns[6] = { (const void *)eval_kernel<true, kPlain>, (const void *)eval_kernel<false, kPlain>,
+        const void *fns[7] = { (const void *)eval_kernel<true, kPlain>, (const void *)eval_kernel<false, kPlain>,
                                (const void *)eval_kernel<true, kSign>, (const void *)eval_kernel<true, kReluOpen>,
+                               (const void *)eval_kernel<false, kSign>,
                                (const void *)gen_kernel<true>, (const void *)gen_kernel<false> };
-        for (int i = 0; i < 6; i++) {
+        for (int i = 0; i < 7; i++) {
             err = hipFuncSetAttribute(fns[i], hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
             if (err != hipSuccess) { g_last_hip_error = (int)err; return FSS_ELAUNCH; }
         }
@@ -444,7 +520,8 @@ static int eval_common(bool cmp, int mode, int party, int n, size_t batch, const
     a.batch = batch; a.n = n; a.party = party;
     const LaunchShape ls = shape_for(batch, dev);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (!cmp) hipLaunchKernelGGL((eval_kernel<false, kPlain>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
+    if (!cmp && mode == kPlain) hipLaunchKernelGGL((eval_kernel<false, kPlain>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
+    else if (!cmp) hipLaunchKernelGGL((eval_kernel<false, kSign>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
     else if (mode == kPlain) hipLaunchKernelGGL((eval_kernel<true, kPlain>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
     else if (mode == kSign) hipLaunchKernelGGL((eval_kernel<true, kSign>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
     else hipLaunchKernelGGL((eval_kernel<true, kReluOpen>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
@@ -455,6 +532,23 @@ static unsigned elementwise_grid(size_t batch)
 {
     size_t g = (batch + 255) / 256;
     return (unsigned)(g < 4096 ? g : 4096);
+}
+
+static uint32_t host_ring_mask(int n) { return n == 32 ? 0xffffffffu : ((1u << n) - 1u); }
+
+static bool bad_u32_ptr(const void *p) { return p == nullptr || misaligned(p, 4); }
+
+// [[y]]_j + [[alpha]]_j with [[alpha]]_j the first plane of a key buffer (Algorithm 5 / wrapper of Algorithm 2)
+static int mask_common(bool cmp, int n, size_t batch, const void *d_key, const uint32_t *d_y_share, uint32_t *d_masked,
+                       fss_stream_t stream)
+{
+    if (bad_n(n)) return FSS_EINVAL;
+    if (batch == 0) return FSS_OK;
+    if (!d_key || misaligned(d_key, 256) || bad_u32_ptr(d_y_share) || bad_u32_ptr(d_masked)) return FSS_EINVAL;
+    const uint32_t *alpha_share = reinterpret_cast<const uint32_t *>(static_cast<const uint8_t *>(d_key) + key_layout(cmp, n, batch).alpha_share);
+    hipLaunchKernelGGL(sign_mask_kernel, dim3(elementwise_grid(batch)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       alpha_share, d_y_share, d_masked, batch, host_ring_mask(n));
+    return check_launch();
 }
 
 }  // namespace fss
@@ -491,15 +585,87 @@ int fss_eq_eval(int party, int n, size_t batch, const void *d_key, const uint32_
 
 int fss_sign_mask(int n, size_t batch, const void *d_key, const uint32_t *d_y_share, uint32_t *d_masked, fss_stream_t stream)
 {
+    return fss::mask_common(true, n, batch, d_key, d_y_share, d_masked, stream);
+}
+
+int fss_eq_mask(int n, size_t batch, const void *d_key, const uint32_t *d_y_share, uint32_t *d_masked, fss_stream_t stream)
+{
+    return fss::mask_common(false, n, batch, d_key, d_y_share, d_masked, stream);
+}
+
+int fss_eq_masked_eval(int party, int n, size_t batch, const void *d_key, const uint32_t *d_masked0, const uint32_t *d_masked1,
+                       uint32_t *d_out, fss_stream_t stream)
+{
+    return fss::eval_common(false, fss::kSign, party, n, batch, d_key, d_masked0, d_masked1, d_out, nullptr, nullptr, nullptr, nullptr, stream);
+}
+
+int fss_argmax_diff_mask(int n, size_t rows, int m, const void *d_cmp_key, const uint32_t *d_x_share, uint32_t *d_masked,
+                         fss_stream_t stream)
+{
+    using namespace fss;
+    if (bad_n(n) || m < 2) return FSS_EINVAL;
+    if (rows == 0) return FSS_OK;
+    if (!d_cmp_key || misaligned(d_cmp_key, 256) || bad_u32_ptr(d_x_share) || bad_u32_ptr(d_masked)) return FSS_EINVAL;
+    const size_t batch = rows * (size_t)m * (size_t)(m - 1);
+    const uint32_t *alpha_share = reinterpret_cast<const uint32_t *>(static_cast<const uint8_t *>(d_cmp_key) + key_layout(true, n, batch).alpha_share);
+    hipLaunchKernelGGL(argmax_diff_mask_kernel, dim3(elementwise_grid(batch)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       alpha_share, d_x_share, d_masked, rows, (uint32_t)m, host_ring_mask(n));
+    return check_launch();
+}
+
+int fss_argmax_count_mask(int party, int n, size_t rows, int m, const uint32_t *d_w_share, const void *d_eq_key,
+                          uint32_t *d_masked, fss_stream_t stream)
+{
+    using namespace fss;
+    if (bad_n(n) || m < 2 || (party != 0 && party != 1)) return FSS_EINVAL;
+    if (rows == 0) return FSS_OK;
+    if (!d_eq_key || misaligned(d_eq_key, 256) || bad_u32_ptr(d_w_share) || bad_u32_ptr(d_masked)) return FSS_EINVAL;
+    const size_t batch = rows * (size_t)m;
+    const uint32_t *alpha_share = reinterpret_cast<const uint32_t *>(static_cast<const uint8_t *>(d_eq_key) + key_layout(false, n, batch).alpha_share);
+    hipLaunchKernelGGL(argmax_count_mask_kernel, dim3(elementwise_grid(batch)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       alpha_share, d_w_share, d_masked, batch, (uint32_t)m, host_ring_mask(n), party);
+    return check_launch();
+}
+
+int fss_maxpool_unroll(size_t channels, int h, int w, int k, int s, const uint32_t *d_x_share, uint32_t *d_rows, fss_stream_t stream)
+{
+    using namespace fss;
+    if (k < 1 || s < 1 || h < k || w < k) return FSS_EINVAL;
+    if (channels == 0) return FSS_OK;
+    if (bad_u32_ptr(d_x_share) || bad_u32_ptr(d_rows)) return FSS_EINVAL;
+    const int oh = (h - k) / s + 1, ow = (w - k) / s + 1;
+    const size_t total = channels * (size_t)oh * ow * k * k;
+    hipLaunchKernelGGL(maxpool_unroll_kernel, dim3(elementwise_grid(total)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       d_x_share, d_rows, channels, h, w, k, s, oh, ow);
+    return check_launch();
+}
+
+int fss_mul_open(int n, size_t count, const uint32_t *d_u_share, const uint32_t *d_v_share, const uint32_t *d_tri_a,
+                 const uint32_t *d_tri_b, uint32_t *d_delta, uint32_t *d_eps, fss_stream_t stream)
+{
     using namespace fss;
     if (bad_n(n)) return FSS_EINVAL;
-    if (batch == 0) return FSS_OK;
-    if (!d_key || !d_y_share || !d_masked) return FSS_EINVAL;
-    if (misaligned(d_key, 256) || misaligned(d_y_share, 4) || misaligned(d_masked, 4)) return FSS_EINVAL;
-    const uint32_t *alpha_share = reinterpret_cast<const uint32_t *>(static_cast<const uint8_t *>(d_key) + key_layout(true, n, batch).alpha_share);
-    const uint32_t mask = n == 32 ? 0xffffffffu : ((1u << n) - 1u);
-    hipLaunchKernelGGL(sign_mask_kernel, dim3(elementwise_grid(batch)), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       alpha_share, d_y_share, d_masked, batch, mask);
+    if (count == 0) return FSS_OK;
+    if (bad_u32_ptr(d_u_share) || bad_u32_ptr(d_v_share) || bad_u32_ptr(d_tri_a) || bad_u32_ptr(d_tri_b) || bad_u32_ptr(d_delta) ||
+        bad_u32_ptr(d_eps))
+        return FSS_EINVAL;
+    hipLaunchKernelGGL(mul_open_kernel, dim3(elementwise_grid(count)), dim3(256), 0, static_cast<hipStream_t>(stream), d_u_share,
+                       d_v_share, d_tri_a, d_tri_b, d_delta, d_eps, count, host_ring_mask(n));
+    return check_launch();
+}
+
+int fss_dot_finish(int party, int n, size_t rows, int m, const uint32_t *d_delta0, const uint32_t *d_delta1, const uint32_t *d_eps0,
+                   const uint32_t *d_eps1, const uint32_t *d_tri_a, const uint32_t *d_tri_b, const uint32_t *d_tri_c,
+                   uint32_t *d_out, fss_stream_t stream)
+{
+    using namespace fss;
+    if (bad_n(n) || m < 1 || (party != 0 && party != 1)) return FSS_EINVAL;
+    if (rows == 0) return FSS_OK;
+    const void *ptrs[8] = { d_delta0, d_delta1, d_eps0, d_eps1, d_tri_a, d_tri_b, d_tri_c, d_out };
+    for (int i = 0; i < 8; i++)
+        if (bad_u32_ptr(ptrs[i])) return FSS_EINVAL;
+    hipLaunchKernelGGL(dot_finish_kernel, dim3(elementwise_grid(rows)), dim3(256), 0, static_cast<hipStream_t>(stream), d_delta0,
+                       d_delta1, d_eps0, d_eps1, d_tri_a, d_tri_b, d_tri_c, d_out, rows, (uint32_t)m, host_ring_mask(n), party);
     return check_launch();
 }
 
