@@ -21,7 +21,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# ---- work model of the comparison Eval kernel ---------------------
+# ---- work model of the comparison Eval kernel ---------------------------------------------
+# (per evaluation at n = 32: 64 AES blocks of 160 four-byte table lookups each; the LDS read port,
+#  128 B/clk/CU, is the unit that binds; the vector ALU and HBM are reported beside it)
 N_BITS = 32
 AES_BLOCKS_PER_EVAL = 2 * N_BITS            # one child block + one sigma/tau block per level
 LOOKUPS_PER_BLOCK = 160                     # 16 table lookups x 10 rounds, 4 bytes each
@@ -245,7 +247,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path runs on ONE GPU (elements are independent; more GPUs would only shard the "
-              "batch with no exchange, see DESIGN.md); run with --gpus 1", file=sys.stderr)
+              "batch with no exchange); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
@@ -344,7 +346,7 @@ def main():
         "gen_key_pairs_per_s": B / (gen_mean * 1e-3),
         "step_evals_per_s_incl_gen": 2 * B / (wall / args.steps),
         # The AES of this path is table-driven out of LDS, and the LDS read port is the unit that
-        # binds (DESIGN.md section 7): 160 four-byte lookups per AES block against 128 B/clk/CU.
+        # binds: 160 four-byte lookups per AES block against 128 B/clk/CU.
         "roofline": {
             "bound": "lds",
             "kernel": "eval_kernel<cmp>",

@@ -7,6 +7,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "../../include/fss.h"
 #include "aes_lds.h"
 #include "key_layout.h"
@@ -413,8 +415,10 @@ struct DeviceInfo {
 
 static int prepare_device(DeviceInfo *info)
 {
-    // per-device, idempotent: raise the dynamic-LDS limit of the four kernels
+    // per-device, idempotent: raise the dynamic-LDS limit of the kernels that hold the tables
     static DeviceInfo cache[64] = {};
+    static std::mutex cache_lock;
+    std::lock_guard<std::mutex> guard(cache_lock);
     int dev = 0;
     hipError_t err = hipGetDevice(&dev);
     if (err != hipSuccess) { g_last_hip_error = (int)err; return FSS_ELAUNCH; }

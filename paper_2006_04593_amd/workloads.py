@@ -178,7 +178,7 @@ def maxpool_round_keys(seed: int, rnd: int, batch: int, n: int = 32) -> GenInput
 
 
 def config_workload(cfg: int, seed: Optional[int] = None, batch: Optional[int] = None) -> Workload:
-    """The workload of benchmark configuration `cfg` (4 returns round 1 only; see maxpool_*)."""
+    """The workload of benchmark configuration `cfg` (4 returns the first of its eight comparison batches only; see maxpool_*)."""
     kind, b = CONFIGS[cfg]
     if batch is not None:
         b = batch

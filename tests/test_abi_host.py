@@ -76,6 +76,38 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
         assert f(32, 0, None, None, None, None, None, None, None) == 0
 
 
+def test_protocol_entry_points_reject_bad_arguments_on_the_host(lib):
+    A = 0x10000
+    assert lib.fss_sign_mask(0, 8, A, A, A, None) == -1
+    assert lib.fss_sign_mask(32, 8, A + 8, A, A, None) == -1
+    assert lib.fss_sign_mask(32, 0, None, None, None, None) == 0
+    assert lib.fss_sign_eval(0, 32, 8, A, A, None, A, None) == -1            # second masked share missing
+    assert lib.fss_relu_open(0, 32, 8, A, A, A, A, A, None, A, A, None) == -1
+    assert lib.fss_relu_open(3, 32, 0, None, None, None, None, None, None, None, None, None) == -1
+    assert lib.fss_relu_finish(0, 32, 8, A, A, A, A, A, A, A, None, None) == -1
+    assert lib.fss_eq_mask(32, 8, A, None, A, None) == -1
+    assert lib.fss_eq_masked_eval(0, 32, 8, A, A, A + 1, A, None) == -1
+    assert lib.fss_argmax_diff_mask(32, 4, 1, A, A, A, None) == -1           # m < 2
+    assert lib.fss_argmax_count_mask(2, 32, 4, 3, A, A, A, None) == -1
+    assert lib.fss_maxpool_unroll(4, 2, 8, 3, 2, A, A, None) == -1            # window larger than the image
+    assert lib.fss_maxpool_unroll(0, 8, 8, 2, 2, None, None, None) == 0
+    assert lib.fss_mul_open(33, 8, A, A, A, A, A, A, None) == -1
+    assert lib.fss_dot_finish(0, 32, 8, 0, A, A, A, A, A, A, A, A, None) == -1
+
+
+def test_streamed_evaluation_arguments(lib):
+    A = 0x10000
+    assert lib.fss_cmp_chunked_key_bytes(32, 1000, 256) == 808 * 1024          # 3 full chunks + 232 padded to 256
+    assert lib.fss_cmp_chunked_key_bytes(32, 1024, 256) == 808 * 1024
+    assert lib.fss_cmp_chunked_key_bytes(32, 1000, 100) == 0                   # chunk must be a multiple of 64
+    assert lib.fss_cmp_chunked_key_bytes(0, 1000, 256) == 0
+    S1, S2 = 0x1000, 0x2000                                                    # stand-ins; validation never dereferences
+    assert lib.fss_cmp_eval_streamed(0, 32, 100, 100, A, A, A, A, S1, S2) == -1
+    assert lib.fss_cmp_eval_streamed(0, 32, 100, 64, A, A, A, A, S1, S1) == -1    # one stream for both roles
+    assert lib.fss_cmp_eval_streamed(0, 32, 100, 64, None, A, A, A, S1, S2) == -1
+    assert lib.fss_cmp_eval_streamed(0, 32, 0, 64, None, None, None, None, S1, S2) == 0
+
+
 def test_strerror(lib):
     assert lib.fss_strerror(0) == b"success"
     for code in (-1, -2, -3, 17):
