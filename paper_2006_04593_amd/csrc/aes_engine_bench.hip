@@ -35,7 +35,9 @@ __global__ __launch_bounds__(kThreads) void lds_engine(uint32_t *out, int iters)
     uint32_t s[4] = { threadIdx.x * 2654435761u, blockIdx.x * 40503u + 1u, threadIdx.x ^ 0x5bd1e995u, 7u };
     for (int it = 0; it < iters; it++) {
         uint32_t g[2][4];
-        const uint32_t in[2][4] = { { s[0], s[1], s[2], s[3] }, { s[0], s[1], s[2], s[3] } };
+        // two independent inputs: the raw engine rate, without the sharing of lookups that blocks
+        // of the same input enjoy in the kernels
+        const uint32_t in[2][4] = { { s[0], s[1], s[2], s[3] }, { s[1], s[2], s[3], s[0] } };
         const uint32_t pk[2] = { 0u - (s[3] & 1u), 0u };
         aes_mmo<-1, 2>(g, in, pk, L);
 #pragma unroll

@@ -121,21 +121,83 @@ __device__ __forceinline__ void issue_column(uint32_t *lk, const uint32_t (&st)[
     lk[3] = lds_load(entry_addr<3>(st[(c + 3) & 3], b23) + kOddTable);
 }
 
-// NB independent AES-128 encryptions per lane, each followed by the Matyas-Meyer-Oseas
-// feed-forward: out[b] = E_{key M_b}(seed[b]) ^ seed[b].  pick[b] (0 or ~0 per lane) is only
-// read by blocks whose key is -1.
+// One table lookup: the contribution of the row-ROW byte to output column c (rounds 1..9).
+template <int ROW>
+__device__ __forceinline__ uint32_t lookup_row(const uint32_t (&st)[4], int c, LaneBase L)
+{
+    const uint32_t base = ROW < 2 ? L.a : L.b;
+    const uint32_t addr = entry_addr<ROW>(st[(c + ROW) & 3], base) + ((ROW & 1) ? kOddTable : 0u);
+    return lds_load(addr);
+}
+
+// Blocks that encrypt the SAME input under keys that differ in few bytes walk through equal
+// state bytes for a while, and equal bytes mean equal lookups.  The three PRG keys differ only
+// in their last byte, so after the first AddRoundKey 15 of 16 state bytes coincide, and after
+// the second (round key 1 differs in 5 bytes, column 0 has diffused) still 8 of 16.
+// shared_lookups(rd, ka, kb): bit 4c + r is set iff, in round rd (1 or 2), the row-r lookup for
+// output column c is the same for a block under PRG key ka and one under PRG key kb.
+// Derived from the round keys at compile time; no property of the keys is assumed.
+constexpr uint32_t rk_byte(int key, int rd, int col, int row) { return (kAes.rk[key][4 * rd + col] >> (8 * row)) & 0xffu; }
+
+constexpr uint32_t shared_lookups(int rd, int ka, int kb)
+{
+    bool eq[4][4] = {};                       // [col][row]: state bytes equal entering round 1
+    for (int col = 0; col < 4; col++)
+        for (int row = 0; row < 4; row++) eq[col][row] = rk_byte(ka, 0, col, row) == rk_byte(kb, 0, col, row);
+    uint32_t mask = 0;
+    for (int step = 1; step <= rd; step++) {
+        mask = 0;
+        for (int c = 0; c < 4; c++)
+            for (int r = 0; r < 4; r++)
+                if (eq[(c + r) & 3][r]) mask |= 1u << (4 * c + r);
+        // state entering the next round: a column is equal where all four of its lookups were
+        // and the next round key agrees
+        bool nxt[4][4] = {};
+        for (int c = 0; c < 4; c++)
+            for (int row = 0; row < 4; row++)
+                nxt[c][row] = ((mask >> (4 * c)) & 0xfu) == 0xfu && rk_byte(ka, step, c, row) == rk_byte(kb, step, c, row);
+        for (int c = 0; c < 4; c++)
+            for (int row = 0; row < 4; row++) eq[c][row] = nxt[c][row];
+    }
+    return mask;
+}
+
+// key id -1 stands for "PRG key 1 or 2, chosen per lane": shared only where both agree
+constexpr uint32_t shared_lookups_any(int rd, int ka, int kb)
+{
+    uint32_t m = 0xffffu;
+    for (int a = (ka < 0 ? 0 : ka); a <= (ka < 0 ? 1 : ka); a++)
+        for (int b = (kb < 0 ? 0 : kb); b <= (kb < 0 ? 1 : kb); b++) m &= shared_lookups(rd, a, b);
+    return m;
+}
+
+// What the tree walk reads of G_3(s): words 0 and 1 (sigma^L, sigma^R) and the two low bits of
+// byte 8 (tau^L, tau^R), i.e. final-round columns 0 and 1 and the row-0 byte of column 2.
+constexpr uint32_t kNeedSigmaTau = 0x01ffu;
+constexpr uint32_t kNeedAll = 0xffffu;
+
+static_assert(shared_lookups(1, 0, 2) == 0xfff7u && shared_lookups(1, 1, 2) == 0xfff7u, "round 1: all but the (column 0, row 3) lookup");
+static_assert(__builtin_popcount(shared_lookups(2, 0, 2)) == 8 && shared_lookups(3, 0, 2) == 0, "round 2: half; round 3: none");
+
+// NB AES-128 encryptions per lane, each followed by the Matyas-Meyer-Oseas feed-forward:
+// out[b] = E_{key M_b}(seed[b]) ^ seed[b].  pick[b] (0 or ~0 per lane) is only read by blocks
+// whose key is -1.  With SAME_INPUT the caller guarantees seed[b] == seed[0] for every b, and
+// blocks b > 0 take the lookups of rounds 1 and 2 that provably equal block 0's from block 0.
 //
 // A wavefront can keep 16 LDS instructions in flight and a round of one block is exactly 16
-// lookups, so the unit of work is a block-round: issue its 16 lookups, then combine.  The
+// lookups, so the unit of work is a block-round: issue its lookups, then combine.  The
 // combine starts with the LAST column, so one wait covers the whole round (fewer
 // instructions on the wave's in-order issue path than a wait per column).
-template <int... M>
-__device__ __forceinline__ void aes_mmo(uint32_t (&out)[sizeof...(M)][4], const uint32_t (&seed)[sizeof...(M)][4],
-                                        const uint32_t (&pick)[sizeof...(M)], LaneBase L)
+// LAST_NEED: which lookups of the final round the caller needs from the LAST block (bit 4c + r as
+// above); output bytes whose lookup is skipped are unspecified.
+template <bool SAME_INPUT, uint32_t LAST_NEED, int... M>
+__device__ __forceinline__ void aes_mmo_impl(uint32_t (&out)[sizeof...(M)][4], const uint32_t (&seed)[sizeof...(M)][4],
+                                             const uint32_t (&pick)[sizeof...(M)], LaneBase L)
 {
     constexpr int NB = sizeof...(M);
     constexpr int keys[NB] = { M... };
     uint32_t st[NB][4];
+    uint32_t lk0[16];                         // block 0's lookups of the current round (rounds 1, 2)
 #pragma unroll
     for (int b = 0; b < NB; b++)
 #pragma unroll
@@ -145,10 +207,29 @@ __device__ __forceinline__ void aes_mmo(uint32_t (&out)[sizeof...(M)][4], const 
 #pragma clang loop unroll(full)
         for (int b = 0; b < NB; b++) {
             uint32_t lk[16];
+            const uint32_t reuse = (SAME_INPUT && b > 0 && r <= 2) ? shared_lookups_any(r, keys[0], keys[b]) : 0u;
 #pragma unroll
             for (int c = 0; c < 4; c++) {
-                if (r < 10) issue_column<false>(&lk[4 * c], st[b], c, L);
-                else issue_column<true>(&lk[4 * c], st[b], c, L);
+                if (r == 10) {
+                    const uint32_t need = (b == NB - 1) ? LAST_NEED : 0xffffu;
+                    if (((need >> (4 * c)) & 0xfu) == 0xfu) {
+                        issue_column<true>(&lk[4 * c], st[b], c, L);
+                    } else {
+                        uint32_t full[4] = { 0, 0, 0, 0 };
+                        if ((need >> (4 * c)) & 0xfu) issue_column<true>(full, st[b], c, L);   // unused rows are dropped as dead code
+#pragma unroll
+                        for (int q = 0; q < 4; q++) lk[4 * c + q] = ((need >> (4 * c + q)) & 1u) ? full[q] : 0u;
+                    }
+                } else {
+                    lk[4 * c + 0] = ((reuse >> (4 * c + 0)) & 1u) ? lk0[4 * c + 0] : lookup_row<0>(st[b], c, L);
+                    lk[4 * c + 1] = ((reuse >> (4 * c + 1)) & 1u) ? lk0[4 * c + 1] : lookup_row<1>(st[b], c, L);
+                    lk[4 * c + 2] = ((reuse >> (4 * c + 2)) & 1u) ? lk0[4 * c + 2] : lookup_row<2>(st[b], c, L);
+                    lk[4 * c + 3] = ((reuse >> (4 * c + 3)) & 1u) ? lk0[4 * c + 3] : lookup_row<3>(st[b], c, L);
+                }
+            }
+            if (SAME_INPUT && b == 0 && r <= 2) {
+#pragma unroll
+                for (int q = 0; q < 16; q++) lk0[q] = lk[q];
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -167,6 +248,28 @@ __device__ __forceinline__ void aes_mmo(uint32_t (&out)[sizeof...(M)][4], const 
             __builtin_amdgcn_sched_barrier(0);
         }
     }
+}
+
+// independent inputs per block
+template <int... M>
+__device__ __forceinline__ void aes_mmo(uint32_t (&out)[sizeof...(M)][4], const uint32_t (&seed)[sizeof...(M)][4],
+                                        const uint32_t (&pick)[sizeof...(M)], LaneBase L)
+{
+    aes_mmo_impl<false, 0xffffu, M...>(out, seed, pick, L);
+}
+
+// every block expands the same seed (one node of the tree under several PRG keys)
+template <uint32_t LAST_NEED, int... M>
+__device__ __forceinline__ void aes_mmo_same_input(uint32_t (&out)[sizeof...(M)][4], const uint32_t (&seed)[4],
+                                                   const uint32_t (&pick)[sizeof...(M)], LaneBase L)
+{
+    constexpr int NB = sizeof...(M);
+    uint32_t in[NB][4];
+#pragma unroll
+    for (int b = 0; b < NB; b++)
+#pragma unroll
+        for (int c = 0; c < 4; c++) in[b][c] = seed[c];
+    aes_mmo_impl<true, LAST_NEED, M...>(out, in, pick, L);
 }
 
 }  // namespace fss

@@ -118,9 +118,8 @@ __global__ __launch_bounds__(kThreads) void eval_kernel(EvalArgs a)
             uint32_t child[4];
             if constexpr (CMP) {
                 uint32_t g[2][4];
-                const uint32_t in[2][4] = { { s[0], s[1], s[2], s[3] }, { s[0], s[1], s[2], s[3] } };
                 const uint32_t pk[2] = { pick, 0u };
-                aes_mmo<-1, 2>(g, in, pk, L);            // G_{1+x[i]}(s) and G_3(s)
+                aes_mmo_same_input<kNeedSigmaTau, -1, 2>(g, s, pk, L);  // G_{1+x[i]}(s) and G_3(s)
                 const uint32_t sigma = ((right ? g[1][1] : g[1][0]) ^ (sigcw & tm)) & mask;
                 const uint32_t tau = ((g[1][2] >> b) ^ (t & ((right ? taucw[1] : taucw[0]) >> i))) & 1u;
                 acc += (tau ? leaf : 0u) + sigma;        // out_i, sign applied at the end
@@ -312,25 +311,22 @@ __global__ __launch_bounds__(kThreads) void gen_kernel(GenArgs a)
 #pragma unroll
                 for (int j = 0; j < 2; j++) {
                     uint32_t h[3][4];
-                    const uint32_t in[3][4] = { { s[j][0], s[j][1], s[j][2], s[j][3] }, { s[j][0], s[j][1], s[j][2], s[j][3] },
-                                                { s[j][0], s[j][1], s[j][2], s[j][3] } };
                     const uint32_t pk[3] = { 0, 0, 0 };
-                    aes_mmo<0, 1, 2>(h, in, pk, L);
+                    aes_mmo_same_input<kNeedSigmaTau, 0, 1, 2>(h, s[j], pk, L);
 #pragma unroll
                     for (int m = 0; m < 3; m++)
 #pragma unroll
                         for (int c = 0; c < 4; c++) g[j][m][c] = h[m][c];
                 }
             } else {
-                uint32_t h[4][4];
-                const uint32_t in[4][4] = { { s[0][0], s[0][1], s[0][2], s[0][3] }, { s[0][0], s[0][1], s[0][2], s[0][3] },
-                                            { s[1][0], s[1][1], s[1][2], s[1][3] }, { s[1][0], s[1][1], s[1][2], s[1][3] } };
-                const uint32_t pk[4] = { 0, 0, 0, 0 };
-                aes_mmo<0, 1, 0, 1>(h, in, pk, L);
 #pragma unroll
-                for (int j = 0; j < 2; j++)
+                for (int j = 0; j < 2; j++) {
+                    uint32_t h[2][4];
+                    const uint32_t pk[2] = { 0, 0 };
+                    aes_mmo_same_input<kNeedAll, 0, 1>(h, s[j], pk, L);
 #pragma unroll
-                    for (int c = 0; c < 4; c++) { g[j][0][c] = h[2 * j][c]; g[j][1][c] = h[2 * j + 1][c]; g[j][2][c] = 0; }
+                    for (int c = 0; c < 4; c++) { g[j][0][c] = h[0][c]; g[j][1][c] = h[1][c]; g[j][2][c] = 0; }
+                }
             }
             // control bits of the children, and the children with that bit cleared
             uint32_t tL[2], tR[2];
