@@ -26,9 +26,11 @@ if ROOT not in sys.path:
 #  128 B/clk/CU, is the unit that binds; the vector ALU and HBM are reported beside it)
 N_BITS = 32
 AES_BLOCKS_PER_EVAL = 2 * N_BITS            # one child block + one sigma/tau block per level
-LOOKUPS_PER_BLOCK = 160                     # 16 table lookups x 10 rounds, 4 bytes each
+LOOKUPS_PER_BLOCK = 160                     # 16 table lookups x 10 rounds, 4 bytes each: what table-driven AES needs
 LDS_BYTES_PER_EVAL = AES_BLOCKS_PER_EVAL * LOOKUPS_PER_BLOCK * 4
-VALU_OPS_PER_BLOCK = 284                    # vector-ALU instructions per AES block (SQ_INSTS_VALU / blocks)
+LDS_BYTES_ISSUED_PER_EVAL = 9282 * 4        # what the kernel issues (SQ_INSTS_LDS): coinciding lookups of the two
+                                            # blocks of a level are shared, unneeded final-round ones skipped
+VALU_OPS_PER_BLOCK = 257                    # vector-ALU instructions per AES block (SQ_INSTS_VALU, tree walk excluded)
 TREE_OPS_PER_LEVEL = 30                     # correction-word gating, selects, accumulate
 LANE_OPS_PER_EVAL = AES_BLOCKS_PER_EVAL * VALU_OPS_PER_BLOCK + N_BITS * TREE_OPS_PER_LEVEL
 HBM_BYTES_PER_EVAL = 804 + 4 + 4            # key planes read by Eval + x + out
@@ -356,6 +358,7 @@ def main():
             "frac": lds_gbs / PEAK_LDS_GBS,
             "traffic": MEASURED_HBM_BYTES_2P22 if B == (1 << 22) else None,
             "traffic_unit": "HBM bytes per Eval launch (rocprofv3 FETCH_SIZE+WRITE_SIZE, scaled)",
+            "lds_issued_frac": B * LDS_BYTES_ISSUED_PER_EVAL / (eval_ms * 1e-3) / 1e9 / PEAK_LDS_GBS,
             "alu": {"achieved": lane_tops, "peak": PEAK_LANE_TOPS, "unit": "T 32-bit lane-ops/s",
                     "frac": lane_tops / PEAK_LANE_TOPS, "lane_ops_per_eval": LANE_OPS_PER_EVAL},
             "hbm": {"achieved": hbm_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": hbm_gbs / PEAK_HBM_GBS,
