@@ -179,74 +179,115 @@ constexpr uint32_t kNeedAll = 0xffffu;
 static_assert(shared_lookups(1, 0, 2) == 0xfff7u && shared_lookups(1, 1, 2) == 0xfff7u, "round 1: all but the (column 0, row 3) lookup");
 static_assert(__builtin_popcount(shared_lookups(2, 0, 2)) == 8 && shared_lookups(3, 0, 2) == 0, "round 2: half; round 3: none");
 
+// byte addresses of the 16 lookups of one block-round (table immediates not included);
+// entries whose bit is set in `skip` are not needed and left untouched
+template <bool LAST>
+__device__ __forceinline__ void lookup_addresses(uint32_t (&ad)[16], const uint32_t (&st)[4], uint32_t skip, LaneBase L)
+{
+    const uint32_t b01 = LAST ? L.b : L.a;   // rows 0,1: tables 0,1 (2,3 in the last round)
+    const uint32_t b23 = LAST ? L.a : L.b;   // rows 2,3: tables 2,3 (0,1 in the last round)
+#pragma unroll
+    for (int c = 0; c < 4; c++) {
+        if (!((skip >> (4 * c + 0)) & 1u)) ad[4 * c + 0] = entry_addr<0>(st[c], b01);
+        if (!((skip >> (4 * c + 1)) & 1u)) ad[4 * c + 1] = entry_addr<1>(st[(c + 1) & 3], b01);
+        if (!((skip >> (4 * c + 2)) & 1u)) ad[4 * c + 2] = entry_addr<2>(st[(c + 2) & 3], b23);
+        if (!((skip >> (4 * c + 3)) & 1u)) ad[4 * c + 3] = entry_addr<3>(st[(c + 3) & 3], b23);
+    }
+}
+
+// s_waitcnt lgkmcnt(0) alone (vmcnt and expcnt fields at their maximum)
+__device__ __forceinline__ void wait_lds() { __builtin_amdgcn_s_waitcnt(0xC07F); }
+
 // NB AES-128 encryptions per lane, each followed by the Matyas-Meyer-Oseas feed-forward:
 // out[b] = E_{key M_b}(seed[b]) ^ seed[b].  pick[b] (0 or ~0 per lane) is only read by blocks
 // whose key is -1.  With SAME_INPUT the caller guarantees seed[b] == seed[0] for every b, and
 // blocks b > 0 take the lookups of rounds 1 and 2 that provably equal block 0's from block 0.
+// LAST_NEED: which lookups of the final round the caller needs from the LAST block (bit 4c + r);
+// output bytes whose lookup is skipped are unspecified.
 //
-// A wavefront can keep 16 LDS instructions in flight and a round of one block is exactly 16
-// lookups, so the unit of work is a block-round: issue its lookups, then combine.  The
-// combine starts with the LAST column, so one wait covers the whole round (fewer
-// instructions on the wave's in-order issue path than a wait per column).
-// LAST_NEED: which lookups of the final round the caller needs from the LAST block (bit 4c + r as
-// above); output bytes whose lookup is skipped are unspecified.
+// Schedule.  A wavefront can keep 16 LDS instructions in flight and a round of one block is
+// exactly 16 lookups, each round needing the whole previous one, so the unit of work is a
+// block-round.  The block-rounds (block 0 round 1, block 1 round 1, ..., block 0 round 2, ...) run
+// as a two-stage pipeline: while the lookups of step k are in flight, the wavefront does the
+// vector-ALU work of its neighbours -- combining step k-1 into the next state and forming the
+// addresses of step k+1 -- and the moment step k's data is back, step k+1's 16 lookups are
+// issued from addresses that are already waiting.  The LDS queue of the wavefront is refilled
+// immediately after every wait instead of after a combine and 16 address computations.
+// (A single block cannot overlap its own rounds; it runs issue / wait / combine.)
 template <bool SAME_INPUT, uint32_t LAST_NEED, int... M>
 __device__ __forceinline__ void aes_mmo_impl(uint32_t (&out)[sizeof...(M)][4], const uint32_t (&seed)[sizeof...(M)][4],
                                              const uint32_t (&pick)[sizeof...(M)], LaneBase L)
 {
     constexpr int NB = sizeof...(M);
     constexpr int keys[NB] = { M... };
+    constexpr int STEPS = 10 * NB;
     uint32_t st[NB][4];
-    uint32_t lk0[16];                         // block 0's lookups of the current round (rounds 1, 2)
+    uint32_t lk[2][16];                       // lookups of step k live in lk[k & 1]
+    uint32_t ad[16];                          // addresses of the next step to issue
 #pragma unroll
     for (int b = 0; b < NB; b++)
 #pragma unroll
         for (int c = 0; c < 4; c++) st[b][c] = add_round_key(keys[b], seed[b][c], 0u, c, pick[b]);
-#pragma clang loop unroll(full)
-    for (int r = 1; r <= 10; r++) {
-#pragma clang loop unroll(full)
-        for (int b = 0; b < NB; b++) {
-            uint32_t lk[16];
-            const uint32_t reuse = (SAME_INPUT && b > 0 && r <= 2) ? shared_lookups_any(r, keys[0], keys[b]) : 0u;
+
+    // which lookups of step k are NOT loaded: shared with block 0 (rounds 1, 2) or not needed (last round)
+    auto skip_of = [&](int k) constexpr -> uint32_t {
+        const int b = k % NB, r = k / NB + 1;
+        if (SAME_INPUT && b > 0 && r <= 2) return shared_lookups_any(r, keys[0], keys[b]);
+        if (r == 10 && b == NB - 1) return ~LAST_NEED & 0xffffu;
+        return 0u;
+    };
+    auto addresses = [&](int k) {
+        const int b = k % NB, r = k / NB + 1;
+        if (r == 10) lookup_addresses<true>(ad, st[b], skip_of(k), L);
+        else lookup_addresses<false>(ad, st[b], skip_of(k), L);
+    };
+    auto issue = [&](int k) {
+        const int b = k % NB, r = k / NB + 1;
+        const uint32_t skip = skip_of(k);
+        uint32_t *dst = lk[k & 1];
+        const uint32_t *blk0 = lk[(k - b) & 1];   // block 0's lookups of the same round (complete by now)
 #pragma unroll
-            for (int c = 0; c < 4; c++) {
-                if (r == 10) {
-                    const uint32_t need = (b == NB - 1) ? LAST_NEED : 0xffffu;
-                    if (((need >> (4 * c)) & 0xfu) == 0xfu) {
-                        issue_column<true>(&lk[4 * c], st[b], c, L);
-                    } else {
-                        uint32_t full[4] = { 0, 0, 0, 0 };
-                        if ((need >> (4 * c)) & 0xfu) issue_column<true>(full, st[b], c, L);   // unused rows are dropped as dead code
-#pragma unroll
-                        for (int q = 0; q < 4; q++) lk[4 * c + q] = ((need >> (4 * c + q)) & 1u) ? full[q] : 0u;
-                    }
-                } else {
-                    lk[4 * c + 0] = ((reuse >> (4 * c + 0)) & 1u) ? lk0[4 * c + 0] : lookup_row<0>(st[b], c, L);
-                    lk[4 * c + 1] = ((reuse >> (4 * c + 1)) & 1u) ? lk0[4 * c + 1] : lookup_row<1>(st[b], c, L);
-                    lk[4 * c + 2] = ((reuse >> (4 * c + 2)) & 1u) ? lk0[4 * c + 2] : lookup_row<2>(st[b], c, L);
-                    lk[4 * c + 3] = ((reuse >> (4 * c + 3)) & 1u) ? lk0[4 * c + 3] : lookup_row<3>(st[b], c, L);
-                }
-            }
-            if (SAME_INPUT && b == 0 && r <= 2) {
-#pragma unroll
-                for (int q = 0; q < 16; q++) lk0[q] = lk[q];
-            }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int cc = 0; cc < 4; cc++) {
-                const int c = 3 - cc;
-                if (r < 10) {
-                    st[b][c] = add_round_key(keys[b], bitop3<kXor3>(lk[4 * c], lk[4 * c + 1], lk[4 * c + 2]),
-                                             lk[4 * c + 3], 4 * r + c, pick[b]);
-                } else {
-                    // last round: SubBytes + ShiftRows only, S(v) = byte r of the row-r lookup
-                    uint32_t lo = __builtin_amdgcn_perm(lk[4 * c + 1], lk[4 * c + 0], 0x0c0c0500u);   // l0.b0, l1.b1, 0, 0
-                    uint32_t hi = __builtin_amdgcn_perm(lk[4 * c + 3], lk[4 * c + 2], 0x07020c0cu);   // 0, 0, l2.b2, l3.b3
-                    out[b][c] = add_round_key(keys[b], bitop3<kOrXor>(lo, hi, seed[b][c]), 0u, 40 + c, pick[b]);
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
+        for (int q = 0; q < 16; q++) {
+            if (!((skip >> q) & 1u)) dst[q] = lds_load(ad[q] + ((q & 1) ? kOddTable : 0u));
+            else if (r == 10) dst[q] = 0u;
+            else dst[q] = blk0[q];
         }
+    };
+    auto combine = [&](int k) {
+        const int b = k % NB, r = k / NB + 1;
+        const uint32_t *v = lk[k & 1];
+#pragma unroll
+        for (int cc = 0; cc < 4; cc++) {
+            const int c = 3 - cc;
+            if (r < 10) {
+                st[b][c] = add_round_key(keys[b], bitop3<kXor3>(v[4 * c], v[4 * c + 1], v[4 * c + 2]), v[4 * c + 3], 4 * r + c, pick[b]);
+            } else {
+                // last round: SubBytes + ShiftRows only, S(v) = byte r of the row-r lookup
+                uint32_t lo = __builtin_amdgcn_perm(v[4 * c + 1], v[4 * c + 0], 0x0c0c0500u);   // l0.b0, l1.b1, 0, 0
+                uint32_t hi = __builtin_amdgcn_perm(v[4 * c + 3], v[4 * c + 2], 0x07020c0cu);   // 0, 0, l2.b2, l3.b3
+                out[b][c] = add_round_key(keys[b], bitop3<kOrXor>(lo, hi, seed[b][c]), 0u, 40 + c, pick[b]);
+            }
+        }
+    };
+
+    addresses(0);
+    issue(0);
+    if (NB > 1) addresses(1);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma clang loop unroll(full)
+    for (int k = 0; k < STEPS; k++) {
+        wait_lds();                               // step k's lookups are back
+        __builtin_amdgcn_sched_barrier(0);
+        if (NB > 1 && k + 1 < STEPS) issue(k + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        combine(k);
+        if (NB > 1) {
+            if (k + 2 < STEPS) addresses(k + 2);
+        } else if (k + 1 < STEPS) {
+            addresses(k + 1);
+            issue(k + 1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
