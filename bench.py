@@ -59,6 +59,15 @@ def cpu_baseline(sample: int):
     t3 = time.perf_counter()
     assert np.array_equal(o0 + o1, (w.x <= g.alpha).astype(np.uint32))
     per_party = ((t2 - t1) + (t3 - t2)) / 2
+    # the same code on one thread, on a sixteenth of the sample
+    small = max(sample // 16, 1)
+    oracle.set_threads(1)
+    t4 = time.perf_counter()
+    k0s, _ = oracle.gen("cmp", N_BITS, g.alpha[:small], g.r[:small], g.seed0[:small], g.seed1[:small])
+    t5 = time.perf_counter()
+    oracle.eval_("cmp", 0, N_BITS, k0s, w.x[:small])
+    t6 = time.perf_counter()
+    oracle.set_threads(0)
     return {
         "value": sample / per_party,
         "unit": "evals/s/party",
@@ -67,6 +76,8 @@ def cpu_baseline(sample: int):
         "sample": f"first-seed {sample} elements of the same workload: cmp Gen {t1 - t0:.2f} s, "
                   f"Eval party0 {t2 - t1:.2f} s, party1 {t3 - t2:.2f} s",
         "gen_pairs_per_s": sample / (t1 - t0),
+        "one_thread_evals_per_s": small / (t6 - t5),
+        "one_thread_gen_pairs_per_s": small / (t5 - t4),
     }
 
 

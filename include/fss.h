@@ -76,13 +76,17 @@ extern "C" {
 
 typedef void *fss_stream_t; /* hipStream_t */
 
+/* Largest element count of one call (2^40; at 808 bytes per element far beyond any device). */
+#define FSS_MAX_BATCH ((size_t)1 << 40)
+
 #define FSS_OK 0
-#define FSS_EINVAL (-1)   /* party not in {0,1}; n not in [1,32]; NULL or misaligned pointer with batch > 0 */
+#define FSS_EINVAL (-1)   /* party not in {0,1}; n not in [1,32]; more than FSS_MAX_BATCH elements; NULL or misaligned pointer with batch > 0 */
 #define FSS_ELAUNCH (-2)  /* the HIP runtime refused a launch or an attribute; see fss_last_hip_error() */
 #define FSS_EDEVICE (-3)  /* current device cannot run the kernels (needs 128 KiB of LDS per workgroup) */
 
 /* Size in bytes of ONE party's key buffer for `batch` elements, padding included
- * (808 * Bp for comparison and 544 * Bp for equality at n = 32).  0 if n is out of range. */
+ * (808 * Bp for comparison and 544 * Bp for equality at n = 32).  0 if n is out of range or
+ * batch exceeds FSS_MAX_BATCH. */
 size_t fss_cmp_key_bytes(int n, size_t batch);
 size_t fss_eq_key_bytes(int n, size_t batch);
 

@@ -445,6 +445,16 @@ static bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintp
 
 static bool bad_n(int n) { return n < 1 || n > 32; }
 
+static bool bad_count(size_t count) { return count > kMaxBatch; }
+
+// a * b as an element count, or kMaxBatch + 1 if it does not fit the limit
+static size_t checked_product(size_t a, size_t b)
+{
+    if (a == 0 || b == 0) return 0;
+    if (a > kMaxBatch || b > kMaxBatch / a) return kMaxBatch + 1;
+    return a * b;
+}
+
 struct LaunchShape {
     unsigned grid, threads;
 };
@@ -475,7 +485,7 @@ static int check_launch()
 static int gen_common(bool cmp, int n, size_t batch, const uint32_t *d_alpha, const uint32_t *d_alpha_r,
                       const uint8_t *d_seed0, const uint8_t *d_seed1, void *d_key0, void *d_key1, fss_stream_t stream)
 {
-    if (bad_n(n)) return FSS_EINVAL;
+    if (bad_n(n) || bad_count(batch)) return FSS_EINVAL;
     if (batch == 0) return FSS_OK;
     if (!d_alpha || !d_alpha_r || !d_seed0 || !d_seed1 || !d_key0 || !d_key1) return FSS_EINVAL;
     if (misaligned(d_alpha, 4) || misaligned(d_alpha_r, 4) || misaligned(d_seed0, 16) || misaligned(d_seed1, 16) ||
@@ -503,7 +513,7 @@ static int eval_common(bool cmp, int mode, int party, int n, size_t batch, const
                        const uint32_t *d_x2, uint32_t *d_out, uint32_t *d_out2, const uint32_t *d_y, const uint32_t *d_ta,
                        const uint32_t *d_tb, fss_stream_t stream)
 {
-    if (bad_n(n) || (party != 0 && party != 1)) return FSS_EINVAL;
+    if (bad_n(n) || (party != 0 && party != 1) || bad_count(batch)) return FSS_EINVAL;
     if (batch == 0) return FSS_OK;
     if (!d_key || !d_x || !d_out) return FSS_EINVAL;
     if (misaligned(d_key, 256) || misaligned(d_x, 4) || misaligned(d_out, 4)) return FSS_EINVAL;
@@ -542,7 +552,7 @@ static bool bad_u32_ptr(const void *p) { return p == nullptr || misaligned(p, 4)
 static int mask_common(bool cmp, int n, size_t batch, const void *d_key, const uint32_t *d_y_share, uint32_t *d_masked,
                        fss_stream_t stream)
 {
-    if (bad_n(n)) return FSS_EINVAL;
+    if (bad_n(n) || bad_count(batch)) return FSS_EINVAL;
     if (batch == 0) return FSS_OK;
     if (!d_key || misaligned(d_key, 256) || bad_u32_ptr(d_y_share) || bad_u32_ptr(d_masked)) return FSS_EINVAL;
     const uint32_t *alpha_share = reinterpret_cast<const uint32_t *>(static_cast<const uint8_t *>(d_key) + key_layout(cmp, n, batch).alpha_share);
@@ -555,9 +565,9 @@ static int mask_common(bool cmp, int n, size_t batch, const void *d_key, const u
 
 extern "C" {
 
-size_t fss_cmp_key_bytes(int n, size_t batch) { return fss::bad_n(n) ? 0 : fss::key_layout(true, n, batch).total; }
+size_t fss_cmp_key_bytes(int n, size_t batch) { return fss::bad_n(n) || fss::bad_count(batch) ? 0 : fss::key_layout(true, n, batch).total; }
 
-size_t fss_eq_key_bytes(int n, size_t batch) { return fss::bad_n(n) ? 0 : fss::key_layout(false, n, batch).total; }
+size_t fss_eq_key_bytes(int n, size_t batch) { return fss::bad_n(n) || fss::bad_count(batch) ? 0 : fss::key_layout(false, n, batch).total; }
 
 int fss_cmp_gen(int n, size_t batch, const uint32_t *d_alpha, const uint32_t *d_alpha_r, const uint8_t *d_seed0,
                 const uint8_t *d_seed1, void *d_key0, void *d_key1, fss_stream_t stream)
@@ -604,9 +614,10 @@ int fss_argmax_diff_mask(int n, size_t rows, int m, const void *d_cmp_key, const
 {
     using namespace fss;
     if (bad_n(n) || m < 2) return FSS_EINVAL;
+    const size_t batch = checked_product(rows, (size_t)m * (size_t)(m - 1));
+    if (bad_count(batch)) return FSS_EINVAL;
     if (rows == 0) return FSS_OK;
     if (!d_cmp_key || misaligned(d_cmp_key, 256) || bad_u32_ptr(d_x_share) || bad_u32_ptr(d_masked)) return FSS_EINVAL;
-    const size_t batch = rows * (size_t)m * (size_t)(m - 1);
     const uint32_t *alpha_share = reinterpret_cast<const uint32_t *>(static_cast<const uint8_t *>(d_cmp_key) + key_layout(true, n, batch).alpha_share);
     hipLaunchKernelGGL(argmax_diff_mask_kernel, dim3(elementwise_grid(batch)), dim3(256), 0, static_cast<hipStream_t>(stream),
                        alpha_share, d_x_share, d_masked, rows, (uint32_t)m, host_ring_mask(n));
@@ -618,9 +629,10 @@ int fss_argmax_count_mask(int party, int n, size_t rows, int m, const uint32_t *
 {
     using namespace fss;
     if (bad_n(n) || m < 2 || (party != 0 && party != 1)) return FSS_EINVAL;
+    const size_t batch = checked_product(rows, (size_t)m);
+    if (bad_count(checked_product(batch, (size_t)(m - 1)))) return FSS_EINVAL;    // the comparison shares it sums
     if (rows == 0) return FSS_OK;
     if (!d_eq_key || misaligned(d_eq_key, 256) || bad_u32_ptr(d_w_share) || bad_u32_ptr(d_masked)) return FSS_EINVAL;
-    const size_t batch = rows * (size_t)m;
     const uint32_t *alpha_share = reinterpret_cast<const uint32_t *>(static_cast<const uint8_t *>(d_eq_key) + key_layout(false, n, batch).alpha_share);
     hipLaunchKernelGGL(argmax_count_mask_kernel, dim3(elementwise_grid(batch)), dim3(256), 0, static_cast<hipStream_t>(stream),
                        alpha_share, d_w_share, d_masked, batch, (uint32_t)m, host_ring_mask(n), party);
@@ -631,10 +643,11 @@ int fss_maxpool_unroll(size_t channels, int h, int w, int k, int s, const uint32
 {
     using namespace fss;
     if (k < 1 || s < 1 || h < k || w < k) return FSS_EINVAL;
+    const int oh = (h - k) / s + 1, ow = (w - k) / s + 1;
+    const size_t total = checked_product(checked_product(channels, checked_product((size_t)oh, (size_t)ow)), checked_product((size_t)k, (size_t)k));
+    if (bad_count(total) || bad_count(checked_product(channels, checked_product((size_t)h, (size_t)w)))) return FSS_EINVAL;
     if (channels == 0) return FSS_OK;
     if (bad_u32_ptr(d_x_share) || bad_u32_ptr(d_rows)) return FSS_EINVAL;
-    const int oh = (h - k) / s + 1, ow = (w - k) / s + 1;
-    const size_t total = channels * (size_t)oh * ow * k * k;
     hipLaunchKernelGGL(maxpool_unroll_kernel, dim3(elementwise_grid(total)), dim3(256), 0, static_cast<hipStream_t>(stream),
                        d_x_share, d_rows, channels, h, w, k, s, oh, ow);
     return check_launch();
@@ -644,7 +657,7 @@ int fss_mul_open(int n, size_t count, const uint32_t *d_u_share, const uint32_t 
                  const uint32_t *d_tri_b, uint32_t *d_delta, uint32_t *d_eps, fss_stream_t stream)
 {
     using namespace fss;
-    if (bad_n(n)) return FSS_EINVAL;
+    if (bad_n(n) || bad_count(count)) return FSS_EINVAL;
     if (count == 0) return FSS_OK;
     if (bad_u32_ptr(d_u_share) || bad_u32_ptr(d_v_share) || bad_u32_ptr(d_tri_a) || bad_u32_ptr(d_tri_b) || bad_u32_ptr(d_delta) ||
         bad_u32_ptr(d_eps))
@@ -659,7 +672,7 @@ int fss_dot_finish(int party, int n, size_t rows, int m, const uint32_t *d_delta
                    uint32_t *d_out, fss_stream_t stream)
 {
     using namespace fss;
-    if (bad_n(n) || m < 1 || (party != 0 && party != 1)) return FSS_EINVAL;
+    if (bad_n(n) || m < 1 || (party != 0 && party != 1) || bad_count(checked_product(rows, (size_t)m))) return FSS_EINVAL;
     if (rows == 0) return FSS_OK;
     const void *ptrs[8] = { d_delta0, d_delta1, d_eps0, d_eps1, d_tri_a, d_tri_b, d_tri_c, d_out };
     for (int i = 0; i < 8; i++)
@@ -688,12 +701,12 @@ int fss_relu_finish(int party, int n, size_t batch, const uint32_t *d_delta0, co
                     uint32_t *d_out, fss_stream_t stream)
 {
     using namespace fss;
-    if (bad_n(n) || (party != 0 && party != 1)) return FSS_EINVAL;
+    if (bad_n(n) || (party != 0 && party != 1) || bad_count(batch)) return FSS_EINVAL;
     if (batch == 0) return FSS_OK;
     const void *ptrs[8] = { d_delta0, d_delta1, d_eps0, d_eps1, d_tri_a, d_tri_b, d_tri_c, d_out };
     for (int i = 0; i < 8; i++)
-        if (!ptrs[i] || misaligned(ptrs[i], 4)) return FSS_EINVAL;
-    const uint32_t mask = n == 32 ? 0xffffffffu : ((1u << n) - 1u);
+        if (bad_u32_ptr(ptrs[i])) return FSS_EINVAL;
+    const uint32_t mask = host_ring_mask(n);
     hipLaunchKernelGGL(relu_finish_kernel, dim3(elementwise_grid(batch)), dim3(256), 0, static_cast<hipStream_t>(stream), d_delta0,
                        d_delta1, d_eps0, d_eps1, d_tri_a, d_tri_b, d_tri_c, d_out, batch, mask, party);
     return check_launch();
@@ -701,7 +714,7 @@ int fss_relu_finish(int party, int n, size_t batch, const uint32_t *d_delta0, co
 
 size_t fss_cmp_chunked_key_bytes(int n, size_t batch, size_t chunk)
 {
-    if (fss::bad_n(n) || chunk == 0 || chunk % 64 != 0) return 0;
+    if (fss::bad_n(n) || fss::bad_count(batch) || fss::bad_count(chunk) || chunk == 0 || chunk % 64 != 0) return 0;
     const size_t full = batch / chunk, rest = batch % chunk;
     return full * fss::key_layout(true, n, chunk).total + (rest ? fss::key_layout(true, n, rest).total : 0);
 }
@@ -710,7 +723,7 @@ int fss_cmp_eval_streamed(int party, int n, size_t batch, size_t chunk, const vo
                           uint32_t *d_out, void *d_staging, fss_stream_t copy_stream, fss_stream_t stream)
 {
     using namespace fss;
-    if (bad_n(n) || (party != 0 && party != 1) || chunk == 0 || chunk % 64 != 0) return FSS_EINVAL;
+    if (bad_n(n) || (party != 0 && party != 1) || bad_count(batch) || bad_count(chunk) || chunk == 0 || chunk % 64 != 0) return FSS_EINVAL;
     if (batch == 0) return FSS_OK;
     if (!h_key_chunks || !d_x || !d_out || !d_staging || misaligned(d_staging, 256) || misaligned(d_x, 4) || misaligned(d_out, 4))
         return FSS_EINVAL;
@@ -757,7 +770,7 @@ const char *fss_strerror(int code)
 {
     switch (code) {
     case FSS_OK: return "success";
-    case FSS_EINVAL: return "invalid argument (party, n, NULL/misaligned/overlapping pointer)";
+    case FSS_EINVAL: return "invalid argument (party, n, element count above 2^40, NULL/misaligned/overlapping pointer)";
     case FSS_ELAUNCH: return "HIP runtime error while preparing or launching a kernel";
     case FSS_EDEVICE: return "device unsupported: kernels need 128 KiB of LDS per workgroup";
     default: return "unknown fss error code";

@@ -13,6 +13,7 @@
 namespace fss {
 
 constexpr size_t kPadElems = 64;  // plane length granularity = one wavefront
+constexpr size_t kMaxBatch = (size_t)1 << 40;   // elements per call; keeps every byte offset far below 2^64
 
 FSS_HD inline size_t padded_batch(size_t batch) { return (batch + kPadElems - 1) / kPadElems * kPadElems; }
 

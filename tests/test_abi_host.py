@@ -42,6 +42,8 @@ def test_key_bytes(lib):
     for n in (0, -1, 33):
         assert fss.cmp_key_bytes(n, 64) == 0 and fss.eq_key_bytes(n, 64) == 0
     assert fss.cmp_key_bytes(32, 0) == 0
+    assert fss.cmp_key_bytes(32, 1 << 40) == 808 << 40     # the largest batch a call takes
+    assert fss.cmp_key_bytes(32, (1 << 40) + 1) == 0 and fss.eq_key_bytes(32, (1 << 64) - 1) == 0
 
 
 def test_key_sizes_agree_with_the_oracle_layout(lib):
@@ -93,6 +95,24 @@ def test_protocol_entry_points_reject_bad_arguments_on_the_host(lib):
     assert lib.fss_maxpool_unroll(0, 8, 8, 2, 2, None, None, None) == 0
     assert lib.fss_mul_open(33, 8, A, A, A, A, A, A, None) == -1
     assert lib.fss_dot_finish(0, 32, 8, 0, A, A, A, A, A, A, A, A, None) == -1
+
+
+def test_element_counts_that_would_overflow_are_rejected(lib):
+    A, B = 0x10000, 0x10000 + (1 << 20)
+    huge = (1 << 40) + 1
+    assert lib.fss_cmp_eval(0, 32, huge, A, A, A, None) == -1
+    assert lib.fss_eq_eval(0, 32, (1 << 64) - 1, A, A, A, None) == -1
+    assert lib.fss_cmp_gen(32, huge, A, A, A, A, A, B, None) == -1
+    assert lib.fss_sign_mask(32, huge, A, A, A, None) == -1
+    assert lib.fss_relu_finish(0, 32, huge, A, A, A, A, A, A, A, A, None) == -1
+    assert lib.fss_mul_open(32, huge, A, A, A, A, A, A, None) == -1
+    assert lib.fss_argmax_diff_mask(32, 1 << 39, 3, A, A, A, None) == -1         # rows * m * (m - 1) > 2^40
+    assert lib.fss_argmax_diff_mask(32, 1 << 62, 4, A, A, A, None) == -1         # would wrap around in 64 bits
+    assert lib.fss_argmax_count_mask(0, 32, 1 << 39, 3, A, A, A, None) == -1
+    assert lib.fss_dot_finish(0, 32, 1 << 39, 9, A, A, A, A, A, A, A, A, None) == -1
+    assert lib.fss_maxpool_unroll(1 << 40, 4, 4, 2, 2, A, A, None) == -1
+    assert lib.fss_cmp_chunked_key_bytes(32, huge, 256) == 0
+    assert lib.fss_cmp_eval_streamed(0, 32, huge, 256, A, A, A, A, None, A) == -1
 
 
 def test_streamed_evaluation_arguments(lib):
