@@ -206,6 +206,15 @@ int fss_cmp_eval_streamed(int party, int n, size_t batch, size_t chunk, const vo
                           const uint32_t *d_x, uint32_t *d_out, void *d_staging,
                           fss_stream_t copy_stream, fss_stream_t stream);
 
+/* Register layouts.  The KeyGen and Eval kernels exist in two layouts with identical results
+ * (keys and shares agree byte for byte): one lane per element (highest throughput) and four
+ * lanes per element (a quarter of the dependent work per wavefront and four times the wavefronts:
+ * lower latency while a batch is too small to fill the device).  The entry points pick by batch
+ * size.  fss_quad_layout_below() returns the batch size below which the current device uses the
+ * four-lane layout (device-dependent: 448 elements per compute unit), or 0 if the device cannot
+ * be queried. */
+size_t fss_quad_layout_below(void);
+
 /* Text for a return code (static storage, never NULL). */
 const char *fss_strerror(int code);
 

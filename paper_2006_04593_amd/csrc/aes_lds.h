@@ -37,17 +37,20 @@ __device__ __forceinline__ uint32_t lds_load(uint32_t byte_addr)
     return *reinterpret_cast<const lds_u32 *>(byte_addr);
 }
 
-__device__ __forceinline__ uint32_t rotl32(uint32_t v, int k) { return k == 0 ? v : __builtin_amdgcn_alignbit(v, v, 32 - k); }
+__device__ __forceinline__ uint32_t rotl32_var(uint32_t v, uint32_t k) { return __builtin_amdgcn_alignbit(v, v, (32u - k) & 31u); }
 
-// Every thread of the workgroup writes its share of the 32768 table words.
+// One unit of work per (table, index) pair: read the entry once, rotate it into table r
+// (te_r = te_0 rotated by r bytes) and write its 32 bank copies as eight 16-byte stores.
+// 1024 units; a workgroup of 1024 threads takes one each.
 __device__ __forceinline__ void fill_tables(uint32_t *lds)
 {
-    for (uint32_t j = threadIdx.x; j < kLdsBytes / 4; j += blockDim.x) {
-        uint32_t region = j >> 14;          // 0: tables 0/1, 1: tables 2/3
-        uint32_t v = (j >> 6) & 255u;       // table index
-        uint32_t odd = (j >> 5) & 1u;
-        uint32_t t = c_aes.te0[v];
-        lds[j] = rotl32(t, 8 * (int)(2 * region + odd));   // te_r = te_0 rotated by r bytes
+    for (uint32_t u = threadIdx.x; u < 1024u; u += blockDim.x) {
+        const uint32_t table = u >> 8, v = u & 255u;
+        const uint32_t t = rotl32_var(c_aes.te0[v], 8 * table);
+        // word offset: region (tables 0/1 or 2/3) | entry | even or odd half of the entry
+        uint4 *dst = reinterpret_cast<uint4 *>(lds + (((table >> 1) << 14) | (v << 6) | ((table & 1u) << 5)));
+#pragma unroll
+        for (int q = 0; q < 8; q++) dst[q] = make_uint4(t, t, t, t);
     }
 }
 

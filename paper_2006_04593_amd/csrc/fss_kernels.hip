@@ -11,6 +11,7 @@
 
 #include "../../include/fss.h"
 #include "aes_lds.h"
+#include "aes_quad.h"
 #include "key_layout.h"
 
 namespace fss {
@@ -154,6 +155,99 @@ __global__ __launch_bounds__(kThreads) void eval_kernel(EvalArgs a)
     }
 }
 
+// The same evaluation with four lanes per element (quad layout of aes_quad.h): lane 4q + c owns
+// word c of the element's seed and of its seed-sized correction words; the scalar pieces of the
+// walk (t, sigma, tau, the accumulator) are kept in all four lanes and lane 4q writes the result.
+// Used for batches that leave CUs short of wavefronts in the one-lane-per-element layout.
+template <bool CMP, int MODE>
+__global__ __launch_bounds__(kThreads) void eval_quad_kernel(EvalArgs a)
+{
+    extern __shared__ uint32_t lds[];
+    fill_tables(lds);
+    __syncthreads();
+    const LaneBase L = lane_base(lds);
+    const QuadKeys K = load_quad_keys();
+    const KeyLayout k = key_layout(CMP, a.n, a.batch);
+    const int n = a.n;
+    const uint32_t mask = ring_mask(n);
+    const uint32_t col = threadIdx.x & 3u;
+    const uint32_t keep = col == 0 ? ~1u : ~0u;           // clears the control bit, which lives in column 0
+    const uint32_t *seed_p = reinterpret_cast<const uint32_t *>(a.key + k.seed);
+    const uint32_t *scw_p = reinterpret_cast<const uint32_t *>(a.key + k.s_cw);
+    const uint32_t *sig_p = reinterpret_cast<const uint32_t *>(a.key + k.sigma_cw);
+    const uint32_t *leaf_p = reinterpret_cast<const uint32_t *>(a.key + k.leaf);
+    const uint32_t *last_p = reinterpret_cast<const uint32_t *>(a.key + k.last);
+
+    // 16-element tiles, dealt to wavefronts like the 64-element tiles of eval_kernel
+    const size_t tiles = (a.batch + 15) / 16;
+    const size_t tile_stride = (size_t)(blockDim.x >> 6) * gridDim.x;
+    for (size_t tile = (size_t)(threadIdx.x >> 6) * gridDim.x + blockIdx.x; tile < tiles; tile += tile_stride) {
+        const size_t e = tile * 16 + ((threadIdx.x & 63u) >> 2);
+        if (e >= a.batch) continue;                      // whole quads drop out together
+        uint32_t s = seed_p[4 * e + col] & keep;
+        uint32_t t = (uint32_t)a.party;
+        uint32_t tcw[2], taucw[2] = { 0, 0 };
+        if constexpr (CMP) {
+            uint4 c = reinterpret_cast<const uint4 *>(a.key + k.ctrl)[e];
+            tcw[0] = c.x; tcw[1] = c.y; taucw[0] = c.z; taucw[1] = c.w;
+        } else {
+            uint2 c = reinterpret_cast<const uint2 *>(a.key + k.ctrl)[e];
+            tcw[0] = c.x; tcw[1] = c.y;
+        }
+        uint32_t xin = a.x[e];
+        if constexpr (MODE != kPlain) xin += a.x2[e];
+        const uint32_t x = xin & mask;
+        uint32_t acc = 0;
+
+        uint32_t scw_next = scw_p[4 * e + col];
+        uint32_t sig_next = 0, leaf_next = 0;
+        if constexpr (CMP) { sig_next = sig_p[e]; leaf_next = leaf_p[e]; }
+        for (int i = 0; i < n; i++) {
+            const uint32_t scw = scw_next, sigcw = sig_next, leaf = leaf_next;
+            if (i + 1 < n) {
+                const size_t pe = (size_t)(i + 1) * k.bp + e;
+                scw_next = scw_p[4 * pe + col];
+                if constexpr (CMP) { sig_next = sig_p[pe]; leaf_next = leaf_p[pe]; }
+            }
+            const uint32_t b = (x >> (n - 1 - i)) & 1u;
+            const bool right = b != 0;
+            const uint32_t pick = 0u - b;
+            const uint32_t tm = 0u - t;
+            uint32_t child;
+            if constexpr (CMP) {
+                uint32_t g[2];
+                const uint32_t in[2] = { s, s };
+                aes_mmo_quad<2, -1, 2>(g, in, pick, K, L);             // G_{1+x[i]}(s) and G_3(s)
+                const uint32_t sigL = quad_broadcast<0>(g[1]), sigR = quad_broadcast<1>(g[1]), w2 = quad_broadcast<2>(g[1]);
+                const uint32_t sigma = ((right ? sigR : sigL) ^ (sigcw & tm)) & mask;
+                const uint32_t tau = ((w2 >> b) ^ (t & ((right ? taucw[1] : taucw[0]) >> i))) & 1u;
+                acc += (tau ? leaf : 0u) + sigma;
+                child = g[0];
+            } else {
+                uint32_t g[1];
+                const uint32_t in[1] = { s };
+                aes_mmo_quad<0, -1>(g, in, pick, K, L);
+                child = g[0];
+            }
+            const uint32_t t_child = quad_broadcast<0>(child) & 1u;
+            s = (child & keep) ^ (scw & tm);
+            t = t_child ^ (t & ((right ? tcw[1] : tcw[0]) >> i) & 1u);
+        }
+        acc += (t ? last_p[e] : 0u) + (quad_broadcast<3>(s) & mask);
+        if (a.party) acc = 0u - acc;
+        acc &= mask;
+        if (col == 0) {
+            if constexpr (MODE == kReluOpen) {
+                const uint32_t v = ((a.party ? 0u : 1u) - acc) & mask;
+                a.out[e] = (a.y_share[e] - a.tri_a[e]) & mask;
+                a.out2[e] = (v - a.tri_b[e]) & mask;
+            } else {
+                a.out[e] = acc;
+            }
+        }
+    }
+}
+
 // [[y]]_j + [[alpha]]_j: the value party j publishes in the Sign protocol (Algorithm 5)
 __global__ void sign_mask_kernel(const uint32_t *alpha_share, const uint32_t *y_share, uint32_t *masked, size_t batch, uint32_t mask)
 {
@@ -255,6 +349,29 @@ __global__ void relu_finish_kernel(const uint32_t *d0, const uint32_t *d1, const
 // KeyGen: Algorithm 1 (CMP = false) and Algorithm 3 (CMP = true), shortened correction words
 // ------------------------------------------------------------------------------------
 
+// padding elements (batch <= e < padded batch): defined (zero) contents in every plane of both keys
+template <bool CMP>
+__device__ __forceinline__ void zero_padding_element(uint8_t *key0, uint8_t *key1, const KeyLayout &k, size_t e, int n)
+{
+#pragma unroll
+    for (int j = 0; j < 2; j++) {
+        uint8_t *kb = j == 0 ? key0 : key1;
+        reinterpret_cast<uint32_t *>(kb + k.alpha_share)[e] = 0;
+        reinterpret_cast<uint4 *>(kb + k.seed)[e] = make_uint4(0, 0, 0, 0);
+        if constexpr (CMP) reinterpret_cast<uint4 *>(kb + k.ctrl)[e] = make_uint4(0, 0, 0, 0);
+        else reinterpret_cast<uint2 *>(kb + k.ctrl)[e] = make_uint2(0, 0);
+        for (int i = 0; i < n; i++) {
+            const size_t pe = (size_t)i * k.bp + e;
+            reinterpret_cast<uint4 *>(kb + k.s_cw)[pe] = make_uint4(0, 0, 0, 0);
+            if constexpr (CMP) {
+                reinterpret_cast<uint32_t *>(kb + k.sigma_cw)[pe] = 0;
+                reinterpret_cast<uint32_t *>(kb + k.leaf)[pe] = 0;
+            }
+        }
+        reinterpret_cast<uint32_t *>(kb + k.last)[e] = 0;
+    }
+}
+
 template <bool CMP>
 __global__ __launch_bounds__(kThreads) void gen_kernel(GenArgs a)
 {
@@ -272,24 +389,7 @@ __global__ __launch_bounds__(kThreads) void gen_kernel(GenArgs a)
     for (size_t tile = (size_t)(threadIdx.x >> 6) * gridDim.x + blockIdx.x; tile < tiles; tile += tile_stride) {
         const size_t e = tile * 64 + (threadIdx.x & 63u);
         if (e >= a.batch) {
-            // padding elements: defined (zero) contents in every plane
-#pragma unroll
-            for (int j = 0; j < 2; j++) {
-                uint8_t *kb = j == 0 ? a.key0 : a.key1;
-                reinterpret_cast<uint32_t *>(kb + k.alpha_share)[e] = 0;
-                reinterpret_cast<uint4 *>(kb + k.seed)[e] = make_uint4(0, 0, 0, 0);
-                if constexpr (CMP) reinterpret_cast<uint4 *>(kb + k.ctrl)[e] = make_uint4(0, 0, 0, 0);
-                else reinterpret_cast<uint2 *>(kb + k.ctrl)[e] = make_uint2(0, 0);
-                for (int i = 0; i < n; i++) {
-                    const size_t pe = (size_t)i * k.bp + e;
-                    reinterpret_cast<uint4 *>(kb + k.s_cw)[pe] = make_uint4(0, 0, 0, 0);
-                    if constexpr (CMP) {
-                        reinterpret_cast<uint32_t *>(kb + k.sigma_cw)[pe] = 0;
-                        reinterpret_cast<uint32_t *>(kb + k.leaf)[pe] = 0;
-                    }
-                }
-                reinterpret_cast<uint32_t *>(kb + k.last)[e] = 0;
-            }
+            zero_padding_element<CMP>(a.key0, a.key1, k, e, n);
             continue;
         }
         const uint32_t alpha = a.alpha[e] & mask;
@@ -398,6 +498,124 @@ __global__ __launch_bounds__(kThreads) void gen_kernel(GenArgs a)
     }
 }
 
+// KeyGen with four lanes per key pair (quad layout of aes_quad.h): lane 4q + c owns word c of
+// both parties' seeds and of the seed-sized correction word; all six PRG blocks of a level (three
+// per party) are in flight together.
+template <bool CMP>
+__global__ __launch_bounds__(kThreads) void gen_quad_kernel(GenArgs a)
+{
+    extern __shared__ uint32_t lds[];
+    fill_tables(lds);
+    __syncthreads();
+    const LaneBase L = lane_base(lds);
+    const QuadKeys K = load_quad_keys();
+    const KeyLayout k = key_layout(CMP, a.n, a.batch);
+    const int n = a.n;
+    const uint32_t mask = ring_mask(n);
+    const uint32_t col = threadIdx.x & 3u;
+    const uint32_t keep = col == 0 ? ~1u : ~0u;
+    uint8_t *const my_key = (col & 1u) ? a.key1 : a.key0;   // scalar planes: lanes 0,2 write k_0, lanes 1,3 write k_1
+    const uint32_t *seed0_w = reinterpret_cast<const uint32_t *>(a.seed0);
+    const uint32_t *seed1_w = reinterpret_cast<const uint32_t *>(a.seed1);
+
+    const size_t tiles = k.bp / 16;
+    const size_t tile_stride = (size_t)(blockDim.x >> 6) * gridDim.x;
+    for (size_t tile = (size_t)(threadIdx.x >> 6) * gridDim.x + blockIdx.x; tile < tiles; tile += tile_stride) {
+        const size_t e = tile * 16 + ((threadIdx.x & 63u) >> 2);
+        if (e >= a.batch) {
+            if (col == 0) zero_padding_element<CMP>(a.key0, a.key1, k, e, n);
+            continue;
+        }
+        const uint32_t alpha = a.alpha[e] & mask;
+        const uint32_t r = a.alpha_r[e] & mask;
+        uint32_t s[2] = { seed0_w[4 * e + col] & keep, seed1_w[4 * e + col] & keep };
+        uint32_t t[2] = { 0u, 1u };
+        uint32_t ctrl[4] = { 0, 0, 0, 0 };
+        reinterpret_cast<uint32_t *>(a.key0 + k.seed)[4 * e + col] = s[0];
+        reinterpret_cast<uint32_t *>(a.key1 + k.seed)[4 * e + col] = s[1];
+
+        for (int i = 0; i < n; i++) {
+            const uint32_t abit = (alpha >> (n - 1 - i)) & 1u;
+            uint32_t g[2][3];                             // [party][G_1, G_2, G_3], this lane's column
+            if constexpr (CMP) {
+                uint32_t h[6];
+                const uint32_t in[6] = { s[0], s[0], s[0], s[1], s[1], s[1] };
+                aes_mmo_quad<3, 0, 1, 2, 0, 1, 2>(h, in, 0u, K, L);
+#pragma unroll
+                for (int j = 0; j < 2; j++)
+#pragma unroll
+                    for (int m = 0; m < 3; m++) g[j][m] = h[3 * j + m];
+            } else {
+                uint32_t h[4];
+                const uint32_t in[4] = { s[0], s[0], s[1], s[1] };
+                aes_mmo_quad<2, 0, 1, 0, 1>(h, in, 0u, K, L);
+#pragma unroll
+                for (int j = 0; j < 2; j++) { g[j][0] = h[2 * j]; g[j][1] = h[2 * j + 1]; g[j][2] = 0; }
+            }
+            uint32_t tL[2], tR[2];
+#pragma unroll
+            for (int j = 0; j < 2; j++) {
+                tL[j] = quad_broadcast<0>(g[j][0]) & 1u; g[j][0] &= keep;
+                tR[j] = quad_broadcast<0>(g[j][1]) & 1u; g[j][1] &= keep;
+            }
+            const uint32_t km = 0u - abit;
+            const uint32_t scw = pick32(km, g[0][0] ^ g[1][0], g[0][1] ^ g[1][1]);
+            const uint32_t tcwL = tL[0] ^ tL[1] ^ abit ^ 1u;
+            const uint32_t tcwR = tR[0] ^ tR[1] ^ abit;
+            ctrl[0] |= tcwL << i;
+            ctrl[1] |= tcwR << i;
+
+            uint32_t sigcw = 0, leaf = 0;
+            if constexpr (CMP) {
+                const uint32_t sgL0 = quad_broadcast<0>(g[0][2]) & mask, sgR0 = quad_broadcast<1>(g[0][2]) & mask;
+                const uint32_t sgL1 = quad_broadcast<0>(g[1][2]) & mask, sgR1 = quad_broadcast<1>(g[1][2]) & mask;
+                const uint32_t w0 = quad_broadcast<2>(g[0][2]), w1 = quad_broadcast<2>(g[1][2]);
+                const uint32_t tauL0 = w0 & 1u, tauR0 = (w0 >> 1) & 1u;
+                const uint32_t tauL1 = w1 & 1u, tauR1 = (w1 >> 1) & 1u;
+                sigcw = pick32(km, sgR0 ^ sgR1, sgL0 ^ sgL1);
+                const uint32_t taucwL = tauL0 ^ tauL1 ^ abit;
+                const uint32_t taucwR = tauR0 ^ tauR1 ^ abit ^ 1u;
+                ctrl[2] |= taucwL << i;
+                ctrl[3] |= taucwR << i;
+                const uint32_t taucw_lose = pick32(km, taucwL, taucwR);
+                const uint32_t sg0 = pick32(km, sgL0, sgR0) ^ (sigcw & (0u - t[0]));
+                const uint32_t sg1 = pick32(km, sgL1, sgR1) ^ (sigcw & (0u - t[1]));
+                const uint32_t tau1 = pick32(km, tauL1, tauR1) ^ (t[1] & taucw_lose);
+                leaf = (abit - sg0 + sg1) & mask;
+                leaf = ((leaf ^ (0u - tau1)) + tau1) & mask;
+            }
+            const uint32_t tcw_keep = pick32(km, tcwR, tcwL);
+#pragma unroll
+            for (int j = 0; j < 2; j++) {
+                s[j] = pick32(km, g[j][1], g[j][0]) ^ (scw & (0u - t[j]));
+                t[j] = pick32(km, tR[j], tL[j]) ^ (t[j] & tcw_keep);
+            }
+            const size_t pe = (size_t)i * k.bp + e;
+            reinterpret_cast<uint32_t *>(a.key0 + k.s_cw)[4 * pe + col] = scw;
+            reinterpret_cast<uint32_t *>(a.key1 + k.s_cw)[4 * pe + col] = scw;
+            if constexpr (CMP) {
+                // one store for the four scalar words: lanes 0,1 sigma_CW of k_0, k_1; lanes 2,3 CW_leaf of k_0, k_1
+                reinterpret_cast<uint32_t *>(my_key + ((col & 2u) ? k.leaf : k.sigma_cw))[pe] = (col & 2u) ? leaf : sigcw;
+            }
+        }
+        const uint32_t c0 = quad_broadcast<3>(s[0]) & mask, c1 = quad_broadcast<3>(s[1]) & mask;
+        uint32_t last = (1u - c0 + c1) & mask;
+        if (t[1]) last = (0u - last) & mask;
+        // lanes 0,1: [[alpha]]_0, [[alpha]]_1; lanes 2,3: CW^(n+1) of k_0, k_1
+        const uint32_t share = (col & 1u) ? ((alpha - r) & mask) : r;
+        reinterpret_cast<uint32_t *>(my_key + ((col & 2u) ? k.last : k.alpha_share))[e] = (col & 2u) ? last : share;
+        if constexpr (CMP) {
+            const uint32_t cw = col == 0 ? ctrl[0] : col == 1 ? ctrl[1] : col == 2 ? ctrl[2] : ctrl[3];
+            reinterpret_cast<uint32_t *>(a.key0 + k.ctrl)[4 * e + col] = cw;
+            reinterpret_cast<uint32_t *>(a.key1 + k.ctrl)[4 * e + col] = cw;
+        } else if (col < 2) {
+            const uint32_t cw = col == 0 ? ctrl[0] : ctrl[1];
+            reinterpret_cast<uint32_t *>(a.key0 + k.ctrl)[2 * e + col] = cw;
+            reinterpret_cast<uint32_t *>(a.key1 + k.ctrl)[2 * e + col] = cw;
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------
@@ -425,11 +643,15 @@ static int prepare_device(DeviceInfo *info)
         if (err == hipSuccess) err = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (err != hipSuccess) { g_last_hip_error = (int)err; return FSS_ELAUNCH; }
         if ((uint32_t)lds < kLdsBytes) { cache[dev].ok = -1; g_last_hip_error = 0; return FSS_EDEVICE; }
-        const void *fns[7] = { (const void *)eval_kernel<true, kPlain>, (const void *)eval_kernel<false, kPlain>,
-                               (const void *)eval_kernel<true, kSign>, (const void *)eval_kernel<true, kReluOpen>,
-                               (const void *)eval_kernel<false, kSign>,
-                               (const void *)gen_kernel<true>, (const void *)gen_kernel<false> };
-        for (int i = 0; i < 7; i++) {
+        const void *fns[] = { (const void *)eval_kernel<true, kPlain>, (const void *)eval_kernel<false, kPlain>,
+                              (const void *)eval_kernel<true, kSign>, (const void *)eval_kernel<true, kReluOpen>,
+                              (const void *)eval_kernel<false, kSign>,
+                              (const void *)eval_quad_kernel<true, kPlain>, (const void *)eval_quad_kernel<false, kPlain>,
+                              (const void *)eval_quad_kernel<true, kSign>, (const void *)eval_quad_kernel<true, kReluOpen>,
+                              (const void *)eval_quad_kernel<false, kSign>,
+                              (const void *)gen_kernel<true>, (const void *)gen_kernel<false>,
+                              (const void *)gen_quad_kernel<true>, (const void *)gen_quad_kernel<false> };
+        for (size_t i = 0; i < sizeof(fns) / sizeof(fns[0]); i++) {
             err = hipFuncSetAttribute(fns[i], hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
             if (err != hipSuccess) { g_last_hip_error = (int)err; return FSS_ELAUNCH; }
         }
@@ -459,21 +681,32 @@ struct LaunchShape {
     unsigned grid, threads;
 };
 
-// One workgroup per CU (its tables take 128 KiB of the CU's LDS); the kernels loop over
-// 64-element tiles.  Every CU gets a workgroup as soon as there are that many tiles, with just
-// enough wavefronts to cover its share (16 at most).
-static LaunchShape shape_for(size_t elems, const DeviceInfo &d)
+// One workgroup per CU (its tables take 128 KiB of the CU's LDS); the kernels loop over tiles of
+// 64 elements (16 in the quad layout).  Every CU gets a workgroup as soon as there are that many
+// tiles, with just enough wavefronts to cover its share (16 at most).
+static LaunchShape shape_for(size_t elems, const DeviceInfo &d, size_t tile_elems = 64)
 {
     const size_t cus = (size_t)d.cus;
-    const size_t tiles = (elems + 63) / 64;
+    const size_t tiles = (elems + tile_elems - 1) / tile_elems;
     const size_t groups = tiles < cus ? tiles : cus;
     size_t waves = (tiles + groups - 1) / groups;
     if (waves > (size_t)kThreads / 64) waves = kThreads / 64;
+    if (waves < 4) waves = 4;       // wavefronts without a tile still help to fill the tables
     LaunchShape s;
     s.threads = (unsigned)(waves * 64);
     s.grid = (unsigned)groups;
     return s;
 }
+
+// The quad layout (four lanes per element) serves batches that would leave the CUs short of
+// wavefronts with one lane per element.  Measured on MI355X, for KeyGen and Eval, comparison and
+// equality alike: the quad layout is faster below about 7 wavefronts of 64 elements per CU (2.7x
+// for Eval and 2x for KeyGen at 16,384 elements), slower above (by 25-30 % on large batches).
+constexpr size_t kQuadBelowWavesPerCu = 7;
+
+static size_t quad_layout_below(const DeviceInfo &d) { return (size_t)d.cus * 64 * kQuadBelowWavesPerCu; }
+
+static bool use_quad_layout(size_t batch, const DeviceInfo &d) { return batch < quad_layout_below(d); }
 
 static int check_launch()
 {
@@ -502,8 +735,14 @@ static int gen_common(bool cmp, int n, size_t batch, const uint32_t *d_alpha, co
     a.seed0 = reinterpret_cast<const uint4 *>(d_seed0); a.seed1 = reinterpret_cast<const uint4 *>(d_seed1);
     a.key0 = static_cast<uint8_t *>(d_key0); a.key1 = static_cast<uint8_t *>(d_key1);
     a.batch = batch; a.n = n;
-    const LaunchShape ls = shape_for(padded_batch(batch), dev);
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (use_quad_layout(batch, dev)) {
+        const LaunchShape ls = shape_for(padded_batch(batch), dev, 16);
+        if (cmp) hipLaunchKernelGGL(gen_quad_kernel<true>, dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
+        else hipLaunchKernelGGL(gen_quad_kernel<false>, dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
+        return check_launch();
+    }
+    const LaunchShape ls = shape_for(padded_batch(batch), dev);
     if (cmp) hipLaunchKernelGGL(gen_kernel<true>, dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
     else hipLaunchKernelGGL(gen_kernel<false>, dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
     return check_launch();
@@ -528,8 +767,17 @@ static int eval_common(bool cmp, int mode, int party, int n, size_t batch, const
     a.key = static_cast<const uint8_t *>(d_key); a.x = d_x; a.x2 = d_x2; a.out = d_out; a.out2 = d_out2;
     a.y_share = d_y; a.tri_a = d_ta; a.tri_b = d_tb;
     a.batch = batch; a.n = n; a.party = party;
-    const LaunchShape ls = shape_for(batch, dev);
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (use_quad_layout(batch, dev)) {
+        const LaunchShape ls = shape_for(batch, dev, 16);
+        if (!cmp && mode == kPlain) hipLaunchKernelGGL((eval_quad_kernel<false, kPlain>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
+        else if (!cmp) hipLaunchKernelGGL((eval_quad_kernel<false, kSign>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
+        else if (mode == kPlain) hipLaunchKernelGGL((eval_quad_kernel<true, kPlain>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
+        else if (mode == kSign) hipLaunchKernelGGL((eval_quad_kernel<true, kSign>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
+        else hipLaunchKernelGGL((eval_quad_kernel<true, kReluOpen>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
+        return check_launch();
+    }
+    const LaunchShape ls = shape_for(batch, dev);
     if (!cmp && mode == kPlain) hipLaunchKernelGGL((eval_kernel<false, kPlain>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
     else if (!cmp) hipLaunchKernelGGL((eval_kernel<false, kSign>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
     else if (mode == kPlain) hipLaunchKernelGGL((eval_kernel<true, kPlain>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
@@ -764,6 +1012,12 @@ int fss_cmp_eval_streamed(int party, int n, size_t batch, size_t chunk, const vo
     if (err == hipSuccess) err = e2 != hipSuccess ? e2 : e3;
     if (err != hipSuccess) { g_last_hip_error = (int)err; return FSS_ELAUNCH; }
     return rc;
+}
+
+size_t fss_quad_layout_below(void)
+{
+    fss::DeviceInfo dev;
+    return fss::prepare_device(&dev) == FSS_OK ? fss::quad_layout_below(dev) : 0;
 }
 
 const char *fss_strerror(int code)

@@ -80,6 +80,48 @@ def test_gen_and_eval_match_oracle(kind, n, batch):
     check_full(kind, n, w.gen, x)
 
 
+# The kernels exist in two register layouts (four lanes per element below
+# fss.quad_layout_below() elements, one lane per element from there on).  The sizes above all
+# fall into the first; these straddle the switch, with ragged tails on both sides.
+@pytest.mark.parametrize("kind", ["cmp", "eq"])
+@pytest.mark.parametrize("n,offset", [(32, -17), (32, -1), (32, 0), (32, 1), (32, 63), (32, 65), (12, 1000), (8, 129), (1, 3)])
+def test_both_layouts_around_the_switch(kind, n, offset):
+    switch = fss.quad_layout_below()
+    assert switch > 0 and switch % 64 == 0
+    batch = switch + offset
+    w = W.uniform_workload(kind, n, batch, seed=7000 + 10 * n + offset)
+    x = w.x.copy()
+    x[::5] = w.gen.alpha[::5]
+    x &= np.uint32(W.ring_mask(n))
+    check_full(kind, n, w.gen, x)
+
+
+def test_the_two_layouts_produce_the_same_bytes():
+    """One set of per-element arguments placed in a batch below the switch and, repeated, in a batch
+    above it: keys and shares of an element depend on that element's arguments only."""
+    n, small = 32, 1000
+    big = fss.quad_layout_below() + 64
+    w = W.uniform_workload("cmp", n, small, seed=4242)
+    rep = -(-big // small)
+    tile = lambda a: np.ascontiguousarray(np.concatenate([a] * rep)[:big])
+    gb = W.GenInputs(n=n, alpha=tile(w.gen.alpha), r=tile(w.gen.r), seed0=tile(w.gen.seed0), seed1=tile(w.gen.seed1))
+    xb = tile(w.x)
+    for kind in ("cmp", "eq"):
+        ks, kb = gpu_gen(kind, n, w.gen), gpu_gen(kind, n, gb)
+        for j in (0, 1):
+            ps = oracle.split_key(kind, n, small, ks[j].cpu().numpy())
+            pb = oracle.split_key(kind, n, big, kb[j].cpu().numpy())
+            for plane in ps:
+                if plane == "bp":
+                    continue
+                a, b = ps[plane], pb[plane]
+                if plane in ("s_cw", "sigma_cw", "leaf"):
+                    assert np.array_equal(a[:, :small], b[:, :small]), (kind, plane)
+                else:
+                    assert np.array_equal(a[:small], b[:small]), (kind, plane)
+            assert np.array_equal(gpu_eval(kind, j, n, ks[j], w.x), gpu_eval(kind, j, n, kb[j], xb)[:small])
+
+
 @pytest.mark.parametrize("kind", ["cmp", "eq"])
 def test_edge_offsets_and_inputs(kind):
     n = 32
