@@ -335,6 +335,7 @@ def main():
     gen_mean = sum(gen_ms) / len(gen_ms)
     evals_per_s = B / (eval_ms * 1e-3)
 
+    lane_layout = B >= fss.quad_layout_below()     # the instruction counts above belong to this layout
     lds_gbs = B * LDS_BYTES_PER_EVAL / (eval_ms * 1e-3) / 1e9
     lane_tops = B * LANE_OPS_PER_EVAL / (eval_ms * 1e-3) / 1e12
     hbm_gbs = B * HBM_BYTES_PER_EVAL / (eval_ms * 1e-3) / 1e9
@@ -351,8 +352,9 @@ def main():
         "vs_baseline": None,
         "dtype": "u32",
         "data": "synthetic",
-        "config": {"workload": f"large batch: cmp Gen of {B} keys + both parties' Eval, n=32, uniform alpha and x, "
-                               "SoA keys resident in HBM", "batch": B, "n": n, "lambda": 128},
+        "config": {"workload": f"{'large' if lane_layout else 'small'} batch: cmp Gen of {B} keys + both parties' Eval, n=32, "
+                               "uniform alpha and x, SoA keys resident in HBM", "batch": B, "n": n, "lambda": 128,
+                   "register_layout": "one lane per element" if lane_layout else "four lanes per element"},
         "eval_ms": eval_ms,
         "eval_ms_min": min(ev_ms),
         "gen_ms": gen_mean,
@@ -369,9 +371,9 @@ def main():
             "frac": lds_gbs / PEAK_LDS_GBS,
             "traffic": MEASURED_HBM_BYTES_2P22 if B == (1 << 22) else None,
             "traffic_unit": "HBM bytes per Eval launch (rocprofv3 FETCH_SIZE+WRITE_SIZE, scaled)",
-            "lds_issued_frac": B * LDS_BYTES_ISSUED_PER_EVAL / (eval_ms * 1e-3) / 1e9 / PEAK_LDS_GBS,
+            "lds_issued_frac": B * LDS_BYTES_ISSUED_PER_EVAL / (eval_ms * 1e-3) / 1e9 / PEAK_LDS_GBS if lane_layout else None,
             "alu": {"achieved": lane_tops, "peak": PEAK_LANE_TOPS, "unit": "T 32-bit lane-ops/s",
-                    "frac": lane_tops / PEAK_LANE_TOPS, "lane_ops_per_eval": LANE_OPS_PER_EVAL},
+                    "frac": lane_tops / PEAK_LANE_TOPS, "lane_ops_per_eval": LANE_OPS_PER_EVAL} if lane_layout else None,
             "hbm": {"achieved": hbm_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": hbm_gbs / PEAK_HBM_GBS,
                     "bytes_per_eval": HBM_BYTES_PER_EVAL},
         },

@@ -3,7 +3,10 @@
 //   2. the same for the ALU-only bit-plane engine (aes_bitplane.h);
 //   3. the machine rates that bound them: conflict-free ds_read_b32 lookups per clock per CU
 //      (the kernel's 32-copy access pattern and an unreplicated table for comparison), and the
-//      issue rate of the vector-ALU instructions both engines are made of.
+//      issue rate of the vector-ALU instructions both engines are made of;
+//   4. the LDS-table engine in its four-lanes-per-block layout (aes_quad.h);
+//   5. whether the vector-memory path could carry some of the lookups beside the LDS (gathers
+//      from a 1-KiB table that stays in the L1 cache).
 // All figures come from HIP events around long launches that fill every CU.
 //
 // usage: aes_engine_bench            (prints a table; exit status 0)
@@ -13,6 +16,7 @@
 
 #include "aes_bitplane.h"
 #include "aes_lds.h"
+#include "aes_quad.h"
 
 #define CK(x)                                                                        \
     do {                                                                             \
@@ -44,6 +48,57 @@ __global__ __launch_bounds__(kThreads) void lds_engine(uint32_t *out, int iters)
         for (int c = 0; c < 4; c++) s[c] = g[0][c] ^ g[1][(c + 1) & 3];
     }
     out[blockIdx.x * blockDim.x + threadIdx.x] = s[0] ^ s[1] ^ s[2] ^ s[3];
+}
+
+// ---- engine 1 in the quad layout: two chained blocks per quad per iteration
+__global__ __launch_bounds__(kThreads) void quad_engine(uint32_t *out, int iters)
+{
+    extern __shared__ uint32_t lds[];
+    fill_tables(lds);
+    __syncthreads();
+    const LaneBase L = lane_base(lds);
+    const QuadKeys K = load_quad_keys();
+    uint32_t s = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 1u;
+    for (int it = 0; it < iters; it++) {
+        uint32_t g[2];
+        const uint32_t in[2] = { s, s ^ 0x9e3779b9u };
+        aes_mmo_quad<0, -1, 2>(g, in, 0u - (quad_broadcast<3>(s) & 1u), K, L);
+        s = g[0] ^ quad_broadcast<1>(g[1]);
+    }
+    out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+// ---- 16 lookups per lane and iteration from pseudo-random bytes, the first G of them as buffer
+// loads from a 1-KiB table in global memory, the others from the LDS tables
+template <int G>
+__global__ __launch_bounds__(kThreads) void gather_mix(uint32_t *out, const uint32_t *table, int iters)
+{
+    extern __shared__ uint32_t lds[];
+    fill_tables(lds);
+    __syncthreads();
+    const LaneBase L = lane_base(lds);
+    __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)table, 0, 1024, 0x00020000);
+    uint32_t r[4];
+    for (int c = 0; c < 4; c++) r[c] = threadIdx.x * 747796405u + blockIdx.x * 2891336453u + 12345u * (c + 1);
+    for (int it = 0; it < iters; it++) {
+        uint32_t v[16];
+#pragma unroll
+        for (int q = 0; q < 16; q++) {
+            const uint32_t w = r[q >> 2];
+            if (q < G) {
+                const uint32_t index = __builtin_amdgcn_perm(w, 0u, 0x0c0c0c04u + (q & 3));
+                v[q] = __builtin_amdgcn_raw_buffer_load_b32(rs, index << 2, 0, 0);
+            } else {
+                const uint32_t base = (q & 2) ? L.b : L.a;
+                const uint32_t addr = __builtin_amdgcn_perm(w, base, 0x03020000u | ((4u + (q & 3)) << 8));
+                v[q] = lds_load(addr + ((q & 1) ? kOddTable : 0u));
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < 4; c++)
+            r[c] = bitop3<kXor3>(bitop3<kXor3>(v[4 * c], v[4 * c + 1], v[4 * c + 2]), v[4 * c + 3], r[(c + 1) & 3]) + 0x9e3779b9u;
+    }
+    out[blockIdx.x * blockDim.x + threadIdx.x] = r[0] ^ r[1] ^ r[2] ^ r[3];
 }
 
 // ---- engine 2: bit planes, eight chained blocks per lane per iteration
@@ -209,6 +264,41 @@ int main()
             printf("  %-26s %8.3f ms  %6.1f T lane-ops/s  %6.1f lanes/clk/CU at %.1f GHz\n", names[op], ms, laneops / (ms * 1e-3) / 1e12,
                    laneops / (ms * 1e-3) / cus / (ghz * 1e9), ghz);
         }
+    }
+
+    printf("\nLDS-table engine, four lanes per block (small-batch layout)\n");
+    {
+        CK(hipFuncSetAttribute((const void *)quad_engine, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes));
+        const int iters = 2000;
+        if (time_launch([&] { hipLaunchKernelGGL(quad_engine, dim3(cus), dim3(kThreads), kLdsBytes, 0, out, iters); }, &ms)) return 1;
+        const double blocks = (double)cus * (kThreads / 4) * iters * 2;
+        printf("  quad layout        %8.3f ms  %7.1f G blocks/s  %5.2f clk/block/CU at %.1f GHz\n", ms, blocks / ms / 1e6,
+               ms * 1e-3 * ghz * 1e9 * cus / blocks, ghz);
+    }
+
+    printf("\n16 lookups per lane and step, G of them gathered from a 1-KiB global table (buffer_load_dword), the rest from LDS\n");
+    {
+        uint32_t *table;
+        CK(hipMalloc(&table, 1024));
+        CK(hipMemset(table, 0x5a, 1024));
+        CK(hipFuncSetAttribute((const void *)gather_mix<0>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes));
+        CK(hipFuncSetAttribute((const void *)gather_mix<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes));
+        CK(hipFuncSetAttribute((const void *)gather_mix<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes));
+        CK(hipFuncSetAttribute((const void *)gather_mix<16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes));
+        const int iters = 4000;
+        const double lookups = (double)cus * kThreads * iters * 16;
+        const int gs[4] = { 0, 1, 2, 16 };
+        for (int i = 0; i < 4; i++) {
+            int rc = 0;
+            if (i == 0) rc = time_launch([&] { hipLaunchKernelGGL(gather_mix<0>, dim3(cus), dim3(kThreads), kLdsBytes, 0, out, table, iters); }, &ms);
+            if (i == 1) rc = time_launch([&] { hipLaunchKernelGGL(gather_mix<1>, dim3(cus), dim3(kThreads), kLdsBytes, 0, out, table, iters); }, &ms);
+            if (i == 2) rc = time_launch([&] { hipLaunchKernelGGL(gather_mix<2>, dim3(cus), dim3(kThreads), kLdsBytes, 0, out, table, iters); }, &ms);
+            if (i == 3) rc = time_launch([&] { hipLaunchKernelGGL(gather_mix<16>, dim3(cus), dim3(kThreads), kLdsBytes, 0, out, table, iters); }, &ms);
+            if (rc) return 1;
+            printf("  G = %2d  %8.3f ms  %6.2f lookups/clk/CU in all, %5.2f of them gathered\n", gs[i], ms,
+                   lookups / (ms * 1e-3) / cus / (ghz * 1e9), lookups * gs[i] / 16 / (ms * 1e-3) / cus / (ghz * 1e9));
+        }
+        CK(hipFree(table));
     }
     CK(hipFree(out));
     return 0;

@@ -39,18 +39,16 @@ __device__ __forceinline__ uint32_t lds_load(uint32_t byte_addr)
 
 __device__ __forceinline__ uint32_t rotl32_var(uint32_t v, uint32_t k) { return __builtin_amdgcn_alignbit(v, v, (32u - k) & 31u); }
 
-// One unit of work per (table, index) pair: read the entry once, rotate it into table r
-// (te_r = te_0 rotated by r bytes) and write its 32 bank copies as eight 16-byte stores.
-// 1024 units; a workgroup of 1024 threads takes one each.
+// The 128 KiB are 8192 chunks of 16 bytes, four copies of one table entry each; chunk c belongs to
+// entry (c >> 4) & 255 of table 2 (c >> 12) + ((c >> 3) & 1) (te_r = te_0 rotated by r bytes).
+// Thread t writes chunks t, t + blockDim.x, ...: consecutive lanes write consecutive chunks.
 __device__ __forceinline__ void fill_tables(uint32_t *lds)
 {
-    for (uint32_t u = threadIdx.x; u < 1024u; u += blockDim.x) {
-        const uint32_t table = u >> 8, v = u & 255u;
-        const uint32_t t = rotl32_var(c_aes.te0[v], 8 * table);
-        // word offset: region (tables 0/1 or 2/3) | entry | even or odd half of the entry
-        uint4 *dst = reinterpret_cast<uint4 *>(lds + (((table >> 1) << 14) | (v << 6) | ((table & 1u) << 5)));
-#pragma unroll
-        for (int q = 0; q < 8; q++) dst[q] = make_uint4(t, t, t, t);
+    uint4 *dst = reinterpret_cast<uint4 *>(lds);
+    for (uint32_t c = threadIdx.x; c < kLdsBytes / 16; c += blockDim.x) {
+        const uint32_t table = ((c >> 12) << 1) | ((c >> 3) & 1u);
+        const uint32_t t = rotl32_var(c_aes.te0[(c >> 4) & 255u], 8 * table);
+        dst[c] = make_uint4(t, t, t, t);
     }
 }
 
