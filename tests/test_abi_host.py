@@ -128,6 +128,11 @@ def test_streamed_evaluation_arguments(lib):
     assert lib.fss_cmp_eval_streamed(0, 32, 0, 64, None, None, None, None, S1, S2) == 0
 
 
+def test_layout_switch_query(lib):
+    # 448 elements per compute unit on a device; 0 where there is none to ask
+    assert lib.fss_quad_layout_below() % (64 * 7) == 0
+
+
 def test_strerror(lib):
     assert lib.fss_strerror(0) == b"success"
     for code in (-1, -2, -3, 17):
