@@ -380,7 +380,6 @@ def main():
     }
     props = torch.cuda.get_device_properties(dev)
     out["device"] = {"name": props.name, "arch": getattr(props, "gcnArchName", None), "compute_units": props.multi_processor_count,
-                     "nominal_clock_mhz": getattr(props, "clock_rate", 0) / 1e3 or None,
                      "lds_per_workgroup": getattr(props, "shared_memory_per_block", None)}
     if args.cpu_sample > 0:
         out["cpu_baseline"] = cpu_baseline(args.cpu_sample)

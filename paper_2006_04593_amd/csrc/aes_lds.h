@@ -108,29 +108,6 @@ __device__ __forceinline__ uint32_t add_round_key(int m, uint32_t acc, uint32_t 
     return bitop3<kXorAnd>(v, pick, kAes.rk[0][idx] ^ kAes.rk[1][idx]);
 }
 
-// The four table lookups that feed output column c of the next round.  lk[r] is the
-// contribution of the row-r byte (ShiftRows: it comes from state column c + r).  Rounds
-// 1..9 read table r; the last round reads table r + 2, whose byte r is S(v).
-template <bool LAST>
-__device__ __forceinline__ void issue_column(uint32_t *lk, const uint32_t (&st)[4], int c, LaneBase L)
-{
-    const uint32_t b01 = LAST ? L.b : L.a;   // rows 0,1: tables 0,1 (2,3 in the last round)
-    const uint32_t b23 = LAST ? L.a : L.b;   // rows 2,3: tables 2,3 (0,1 in the last round)
-    lk[0] = lds_load(entry_addr<0>(st[c], b01));
-    lk[1] = lds_load(entry_addr<1>(st[(c + 1) & 3], b01) + kOddTable);
-    lk[2] = lds_load(entry_addr<2>(st[(c + 2) & 3], b23));
-    lk[3] = lds_load(entry_addr<3>(st[(c + 3) & 3], b23) + kOddTable);
-}
-
-// One table lookup: the contribution of the row-ROW byte to output column c (rounds 1..9).
-template <int ROW>
-__device__ __forceinline__ uint32_t lookup_row(const uint32_t (&st)[4], int c, LaneBase L)
-{
-    const uint32_t base = ROW < 2 ? L.a : L.b;
-    const uint32_t addr = entry_addr<ROW>(st[(c + ROW) & 3], base) + ((ROW & 1) ? kOddTable : 0u);
-    return lds_load(addr);
-}
-
 // Blocks that encrypt the SAME input under keys that differ in few bytes walk through equal
 // state bytes for a while, and equal bytes mean equal lookups.  The three PRG keys differ only
 // in their last byte, so after the first AddRoundKey 15 of 16 state bytes coincide, and after
@@ -180,8 +157,10 @@ constexpr uint32_t kNeedAll = 0xffffu;
 static_assert(shared_lookups(1, 0, 2) == 0xfff7u && shared_lookups(1, 1, 2) == 0xfff7u, "round 1: all but the (column 0, row 3) lookup");
 static_assert(__builtin_popcount(shared_lookups(2, 0, 2)) == 8 && shared_lookups(3, 0, 2) == 0, "round 2: half; round 3: none");
 
-// byte addresses of the 16 lookups of one block-round (table immediates not included);
-// entries whose bit is set in `skip` are not needed and left untouched
+// Byte addresses of the 16 lookups of one block-round (table immediates not included).  Lookup
+// 4c + r is the contribution of the row-r byte to output column c (ShiftRows: it comes from state
+// column c + r).  Rounds 1..9 read table r; the last round reads table r + 2, whose byte r is S(v).
+// Entries whose bit is set in `skip` are not needed and left untouched.
 template <bool LAST>
 __device__ __forceinline__ void lookup_addresses(uint32_t (&ad)[16], const uint32_t (&st)[4], uint32_t skip, LaneBase L)
 {
