@@ -123,6 +123,42 @@ def test_the_two_layouts_produce_the_same_bytes():
 
 
 @pytest.mark.parametrize("kind", ["cmp", "eq"])
+@pytest.mark.parametrize("n,batch", [(32, 1), (32, 65), (12, 1000), (32, None)])
+def test_nothing_is_written_outside_the_buffers(kind, n, batch):
+    """Key and output buffers sit between guard regions inside larger allocations; Gen and Eval must
+    leave the guards alone (batch None = just above the switch of register layouts, ragged)."""
+    if batch is None:
+        batch = fss.quad_layout_below() + 77
+    print(f"case guards kind={kind} n={n} batch={batch}", flush=True)
+    guard = 4096
+    w = W.uniform_workload(kind, n, batch, seed=31 * n + batch)
+    g = w.gen
+    nbytes = key_bytes(kind, n, batch)
+    arena = torch.full((2 * nbytes + 3 * guard,), 0xC3, dtype=torch.uint8, device=dev())
+    k0 = arena[guard:guard + nbytes]
+    k1 = arena[2 * guard + nbytes:2 * guard + 2 * nbytes]
+    assert k0.data_ptr() % 256 == 0 and k1.data_ptr() % 256 == 0
+    gen = fss.cmp_gen if kind == "cmp" else fss.eq_gen
+    gen(n, batch, to_dev(g.alpha), to_dev(g.r), to_dev(g.seed0), to_dev(g.seed1), k0, k1)
+    outs = torch.full((2 * batch + 3 * 1024,), 0x3C3C3C3C, dtype=torch.int32, device=dev())
+    o0, o1 = outs[1024:1024 + batch], outs[2048 + batch:2048 + 2 * batch]
+    ev = fss.cmp_eval if kind == "cmp" else fss.eq_eval
+    xd = to_dev(w.x)
+    ev(0, n, batch, k0, xd, o0)
+    ev(1, n, batch, k1, xd, o1)
+    torch.cuda.synchronize()
+    a = arena.cpu().numpy()
+    for lo, hi in ((0, guard), (guard + nbytes, 2 * guard + nbytes), (2 * guard + 2 * nbytes, 3 * guard + 2 * nbytes)):
+        assert (a[lo:hi] == 0xC3).all(), f"key guard [{lo},{hi}) was written"
+    o = outs.cpu().numpy()
+    for lo, hi in ((0, 1024), (1024 + batch, 2048 + batch), (2048 + 2 * batch, 3072 + 2 * batch)):
+        assert (o[lo:hi] == 0x3C3C3C3C).all(), f"output guard [{lo},{hi}) was written"
+    r0, r1 = oracle.gen(kind, n, g.alpha, g.r, g.seed0, g.seed1)
+    assert np.array_equal(a[guard:guard + nbytes], r0) and np.array_equal(a[2 * guard + nbytes:2 * guard + 2 * nbytes], r1)
+    assert np.array_equal(u32(o0), oracle.eval_(kind, 0, n, r0, w.x)) and np.array_equal(u32(o1), oracle.eval_(kind, 1, n, r1, w.x))
+
+
+@pytest.mark.parametrize("kind", ["cmp", "eq"])
 def test_edge_offsets_and_inputs(kind):
     n = 32
     edges = W.edge_inputs(n)
