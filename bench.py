@@ -10,6 +10,9 @@ HBM before the timed region.  Prints ONE JSON line.
   roofline   the dominant kernel (comparison Eval) against the LDS read peak that binds it,
              with the vector-ALU and HBM fractions beside it
   cpu_baseline  the plain-C oracle timed on this host's cores on a bounded sample
+
+Other lines on request: --batch N (small batches run the four-lanes-per-element kernels),
+--workload eq (equality keys), --workload relu / maxpool (the paper's layers around the path).
 """
 import argparse
 import json
@@ -250,8 +253,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--batch", type=int, default=1 << 22, help="elements per step (default: the 2^22 configuration)")
     ap.add_argument("--cpu-sample", type=int, default=1 << 18, help="elements for the oracle timing; 0 skips it")
-    ap.add_argument("--workload", choices=["large", "relu", "maxpool"], default="large",
-                    help="large: the headline 2^22 comparison Gen+Eval step; relu: one shared ReLU layer of "
+    ap.add_argument("--workload", choices=["large", "eq", "relu", "maxpool"], default="large",
+                    help="large: the headline 2^22 comparison Gen+Eval step; eq: the same step with the equality keys "
+                         "(Algorithms 1 and 2; --batch 1048576 is the 2^20 configuration); relu: one shared ReLU layer of "
                          "64x112x112 activations (Sign mask, fused comparison+open round, finish) per party; "
                          "maxpool: the paper's MaxPool (Algorithm 7), 3x3 stride 2 over 64x112x112")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -279,11 +283,16 @@ def main():
         print(json.dumps(maxpool_layer_bench(args, dev)))
         return
     B, n = args.batch, N_BITS
-    w = W.uniform_workload("cmp", n, B, seed=W.BASE_SEED + 5, name="config5")
+    cmp = args.workload != "eq"
+    if cmp:
+        w = W.uniform_workload("cmp", n, B, seed=W.BASE_SEED + 5, name="config5")
+    else:
+        w = W.equality_workload(n, B, seed=W.BASE_SEED + 2)           # x = alpha on a seeded tenth of the elements
     g = w.gen
+    gen_fn, eval_fn, key_bytes_fn = (fss.cmp_gen, fss.cmp_eval, fss.cmp_key_bytes) if cmp else (fss.eq_gen, fss.eq_eval, fss.eq_key_bytes)
     d_alpha, d_r, d_x = (torch.from_numpy(a.view(np.int32)).to(dev) for a in (g.alpha, g.r, w.x))
     d_s0, d_s1 = torch.from_numpy(g.seed0).to(dev), torch.from_numpy(g.seed1).to(dev)
-    nbytes = fss.cmp_key_bytes(n, B)
+    nbytes = key_bytes_fn(n, B)
     k0 = torch.empty(nbytes, dtype=torch.uint8, device=dev)
     k1 = torch.empty(nbytes, dtype=torch.uint8, device=dev)
     o0 = torch.empty(B, dtype=torch.int32, device=dev)
@@ -297,13 +306,13 @@ def main():
         if marks is not None:
             e = [ev() for _ in range(4)]
             e[0].record(stream)
-        fss.cmp_gen(n, B, d_alpha, d_r, d_s0, d_s1, k0, k1, stream=stream)
+        gen_fn(n, B, d_alpha, d_r, d_s0, d_s1, k0, k1, stream=stream)
         if marks is not None:
             e[1].record(stream)
-        fss.cmp_eval(0, n, B, k0, d_x, o0, stream=stream)
+        eval_fn(0, n, B, k0, d_x, o0, stream=stream)
         if marks is not None:
             e[2].record(stream)
-        fss.cmp_eval(1, n, B, k1, d_x, o1, stream=stream)
+        eval_fn(1, n, B, k1, d_x, o1, stream=stream)
         if marks is not None:
             e[3].record(stream)
             marks.append(e)
@@ -327,7 +336,8 @@ def main():
 
     # correctness of what was just timed: reconstruction on every element
     rec = (o0 + o1).cpu().numpy().view(np.uint32)
-    assert np.array_equal(rec, (w.x <= g.alpha).astype(np.uint32)), "reconstruction failed"
+    truth = (w.x <= g.alpha) if cmp else (w.x == g.alpha)
+    assert np.array_equal(rec, truth.astype(np.uint32)), "reconstruction failed"
 
     gen_ms = [e[0].elapsed_time(e[1]) for e in marks]
     ev_ms = [e[1].elapsed_time(e[2]) for e in marks] + [e[2].elapsed_time(e[3]) for e in marks]
@@ -336,11 +346,13 @@ def main():
     evals_per_s = B / (eval_ms * 1e-3)
 
     lane_layout = B >= fss.quad_layout_below()     # the instruction counts above belong to this layout
-    lds_gbs = B * LDS_BYTES_PER_EVAL / (eval_ms * 1e-3) / 1e9
+    blocks = AES_BLOCKS_PER_EVAL if cmp else N_BITS                 # equality: one block per level
+    hbm_per_eval = HBM_BYTES_PER_EVAL if cmp else 540 + 4 + 4       # equality key planes read by Eval + x + out
+    lds_gbs = B * blocks * LOOKUPS_PER_BLOCK * 4 / (eval_ms * 1e-3) / 1e9
     lane_tops = B * LANE_OPS_PER_EVAL / (eval_ms * 1e-3) / 1e12
-    hbm_gbs = B * HBM_BYTES_PER_EVAL / (eval_ms * 1e-3) / 1e9
+    hbm_gbs = B * hbm_per_eval / (eval_ms * 1e-3) / 1e9
     out = {
-        "metric": "FSS comparison evals/sec per party (n=32, lambda=128)",
+        "metric": f"FSS {'comparison' if cmp else 'equality'} evals/sec per party (n=32, lambda=128)",
         "value": evals_per_s,
         "unit": "evals/s/party",
         "n_gpus": 1,
@@ -352,8 +364,8 @@ def main():
         "vs_baseline": None,
         "dtype": "u32",
         "data": "synthetic",
-        "config": {"workload": f"{'large' if lane_layout else 'small'} batch: cmp Gen of {B} keys + both parties' Eval, n=32, "
-                               "uniform alpha and x, SoA keys resident in HBM", "batch": B, "n": n, "lambda": 128,
+        "config": {"workload": f"{'large' if lane_layout else 'small'} batch: {'cmp' if cmp else 'eq'} Gen of {B} keys + both parties' Eval, n=32, "
+                               + ("uniform alpha and x" if cmp else "uniform alpha, x = alpha on a tenth of the elements") + ", SoA keys resident in HBM", "batch": B, "n": n, "lambda": 128,
                    "register_layout": "one lane per element" if lane_layout else "four lanes per element"},
         "eval_ms": eval_ms,
         "eval_ms_min": min(ev_ms),
@@ -364,24 +376,24 @@ def main():
         # binds: 160 four-byte lookups per AES block against 128 B/clk/CU.
         "roofline": {
             "bound": "lds",
-            "kernel": "eval_kernel<cmp>",
+            "kernel": "eval_kernel<cmp>" if cmp else "eval_kernel<eq>",
             "achieved": lds_gbs,
             "peak": PEAK_LDS_GBS,
             "unit": "GB/s",
             "frac": lds_gbs / PEAK_LDS_GBS,
-            "traffic": MEASURED_HBM_BYTES_2P22 if B == (1 << 22) else None,
+            "traffic": MEASURED_HBM_BYTES_2P22 if (cmp and B == (1 << 22)) else None,
             "traffic_unit": "HBM bytes per Eval launch (rocprofv3 FETCH_SIZE+WRITE_SIZE, scaled)",
-            "lds_issued_frac": B * LDS_BYTES_ISSUED_PER_EVAL / (eval_ms * 1e-3) / 1e9 / PEAK_LDS_GBS if lane_layout else None,
+            "lds_issued_frac": B * LDS_BYTES_ISSUED_PER_EVAL / (eval_ms * 1e-3) / 1e9 / PEAK_LDS_GBS if (cmp and lane_layout) else None,
             "alu": {"achieved": lane_tops, "peak": PEAK_LANE_TOPS, "unit": "T 32-bit lane-ops/s",
-                    "frac": lane_tops / PEAK_LANE_TOPS, "lane_ops_per_eval": LANE_OPS_PER_EVAL} if lane_layout else None,
+                    "frac": lane_tops / PEAK_LANE_TOPS, "lane_ops_per_eval": LANE_OPS_PER_EVAL} if (cmp and lane_layout) else None,
             "hbm": {"achieved": hbm_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": hbm_gbs / PEAK_HBM_GBS,
-                    "bytes_per_eval": HBM_BYTES_PER_EVAL},
+                    "bytes_per_eval": hbm_per_eval},
         },
     }
     props = torch.cuda.get_device_properties(dev)
     out["device"] = {"name": props.name, "arch": getattr(props, "gcnArchName", None), "compute_units": props.multi_processor_count,
                      "lds_per_workgroup": getattr(props, "shared_memory_per_block", None)}
-    if args.cpu_sample > 0:
+    if args.cpu_sample > 0 and cmp:
         out["cpu_baseline"] = cpu_baseline(args.cpu_sample)
     print(json.dumps(out))
 
