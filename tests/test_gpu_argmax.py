@@ -88,7 +88,8 @@ def same(a, b, names):
             assert np.array_equal(np.asarray(a[name][j]).reshape(-1), np.asarray(b[name][j]).reshape(-1)), (name, j)
 
 
-@pytest.mark.parametrize("n,rows,m", [(32, 1, 2), (32, 100, 10), (16, 257, 4), (32, 64, 9), (12, 31, 3)])
+# the last case is large enough for both evaluations (921,600 comparisons, 115,200 equalities) to run one lane per element
+@pytest.mark.parametrize("n,rows,m", [(32, 1, 2), (32, 100, 10), (16, 257, 4), (32, 64, 9), (12, 31, 3), (32, 12800, 9)])
 def test_argmax_matches_oracle(n, rows, m):
     print(f"case argmax n={n} rows={rows} m={m}", flush=True)
     rng = np.random.default_rng(n * 100 + rows + m)
