@@ -246,6 +246,79 @@ def maxpool_layer_bench(args, dev):
     }
 
 
+def dependent_rounds_bench(args, dev):
+    """Benchmark configuration 4: a 3x3 stride-2 pad-1 max-pool of 64 x 112 x 112 activations as a running
+    maximum, eight DEPENDENT comparison rounds of 200,704 elements (round k compares the running
+    maximum with tap k under fresh keys).  The reveal and the update between rounds are done in the
+    clear by a few torch ops: they stand in for the protocol's messages and are not part of the method."""
+    import numpy as np
+    import torch
+
+    import paper_2006_04593_amd as fss
+    from paper_2006_04593_amd import workloads as W
+
+    n = N_BITS
+    taps = W.maxpool_taps(W.BASE_SEED + 4)                       # [9, B] int64
+    B = taps.shape[1]
+
+    def T(a):
+        return torch.from_numpy(a.view(np.int32) if a.dtype == np.uint32 else a).to(dev)
+
+    d_taps = [T((taps[k] & 0xFFFFFFFF).astype(np.uint32)) for k in range(9)]
+    keys, d_alpha = [], []
+    for rnd in range(1, W.MAXPOOL_ROUNDS + 1):
+        g = W.maxpool_round_keys(W.BASE_SEED + 4, rnd, B)
+        kk = [torch.empty(fss.cmp_key_bytes(n, B), dtype=torch.uint8, device=dev) for _ in range(2)]
+        fss.cmp_gen(n, B, T(g.alpha), T(g.r), T(g.seed0), T(g.seed1), kk[0], kk[1])
+        keys.append(kk)
+        d_alpha.append(T(g.alpha))
+    torch.cuda.synchronize()
+    o = [torch.empty(B, dtype=torch.int32, device=dev) for _ in range(2)]
+    stream = torch.cuda.current_stream()
+    marks = []
+
+    def step(timed):
+        m = d_taps[0].clone()
+        for k in range(1, 9):
+            x = m - d_taps[k] + d_alpha[k - 1]                  # the value both parties would reveal: (m - w_k) + alpha_k
+            for j in (0, 1):
+                if timed:
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                fss.cmp_eval(j, n, B, keys[k - 1][j], x, o[j], stream=stream)
+                if timed:
+                    e1.record(stream)
+                    marks.append((e0, e1))
+            m = torch.where((o[0] + o[1]) == 1, d_taps[k], m)   # 1{m - w_k <= 0}: the tap is at least the running maximum
+        return m
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        m = step(True)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    got = m.cpu().numpy().astype(np.int64)
+    agree = (got == taps.max(axis=0)).mean()
+    assert agree > 0.9999, f"running maximum agrees with the plain max-pool on {agree} of the outputs"
+    ms = [a.elapsed_time(b) for a, b in marks]
+    eval_ms = sum(ms) / len(ms)
+    lds_gbs = B * LDS_BYTES_PER_EVAL / (eval_ms * 1e-3) / 1e9
+    return {
+        "metric": "FSS comparison evals/sec per party in dependent rounds (n=32, lambda=128)",
+        "value": B / (eval_ms * 1e-3), "unit": "evals/s/party", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32", "data": "synthetic",
+        "config": {"workload": f"running-maximum max-pool 3x3/2 of 64x112x112: 8 dependent rounds x both parties' Eval of {B} elements",
+                   "batch": B, "rounds": 8, "n": n, "lambda": 128},
+        "eval_ms": eval_ms, "eval_ms_sum_of_16": eval_ms * 16, "agreement_with_plain_maxpool": agree,
+        "roofline": {"bound": "lds", "kernel": "eval_kernel<cmp>", "achieved": lds_gbs, "peak": PEAK_LDS_GBS,
+                     "unit": "GB/s", "frac": lds_gbs / PEAK_LDS_GBS, "traffic": None},
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -253,11 +326,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--batch", type=int, default=1 << 22, help="elements per step (default: the 2^22 configuration)")
     ap.add_argument("--cpu-sample", type=int, default=1 << 18, help="elements for the oracle timing; 0 skips it")
-    ap.add_argument("--workload", choices=["large", "eq", "relu", "maxpool"], default="large",
+    ap.add_argument("--workload", choices=["large", "eq", "relu", "maxpool", "rounds"], default="large",
                     help="large: the headline 2^22 comparison Gen+Eval step; eq: the same step with the equality keys "
                          "(Algorithms 1 and 2; --batch 1048576 is the 2^20 configuration); relu: one shared ReLU layer of "
                          "64x112x112 activations (Sign mask, fused comparison+open round, finish) per party; "
-                         "maxpool: the paper's MaxPool (Algorithm 7), 3x3 stride 2 over 64x112x112")
+                         "maxpool: the paper's MaxPool (Algorithm 7), 3x3 stride 2 over 64x112x112; rounds: the same "
+                         "pooling as a running maximum, 8 dependent comparison rounds of 200,704 elements")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also launch one plain elementwise copy over 1 GiB, so that a rocprofv3 --pmc run of this "
                          "command holds the counter's reading for a kernel of known traffic")
@@ -281,6 +355,9 @@ def main():
         return
     if args.workload == "maxpool":
         print(json.dumps(maxpool_layer_bench(args, dev)))
+        return
+    if args.workload == "rounds":
+        print(json.dumps(dependent_rounds_bench(args, dev)))
         return
     B, n = args.batch, N_BITS
     cmp = args.workload != "eq"
