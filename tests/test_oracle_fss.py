@@ -272,3 +272,92 @@ def test_maxpool_taps_cover_plain_maxpool():
     p[:, 1:-1, 1:-1] = a
     want = np.stack([p[:, 2 * i:2 * i + 3, 2 * j:2 * j + 3].max(axis=(1, 2)) for i in range(4) for j in range(4)], axis=1)
     assert np.array_equal(taps.max(axis=0).reshape(2, 16), want)
+
+
+# ---------------------------------------------------------------- one party's view
+
+@pytest.mark.parametrize("kind", ["cmp", "eq"])
+def test_one_partys_share_and_key_say_nothing_about_the_result(kind):
+    """Def. 2.1, security: k_j alone hides alpha.  A statistical shadow of it that a bug could break
+    while every sum still reconstructs: a single party's shares are uniform over the ring whether
+    f(x) is 0 or 1, and the published correction words are uniform bytes."""
+    n, batch = 32, 1 << 15
+    rng = np.random.default_rng(2718)
+    g = W.gen_inputs(rng, n, batch)
+    x = np.where(rng.random(batch) < 0.5, g.alpha, W.uniform_ring(rng, n, batch)).astype(np.uint32)
+    if kind == "cmp":
+        x = np.where(rng.random(batch) < 0.5, g.alpha - rng.integers(0, 1000, batch).astype(np.uint32), g.alpha + rng.integers(1, 1000, batch).astype(np.uint32)).astype(np.uint32)
+    k0, k1 = oracle.gen(kind, n, g.alpha, g.r, g.seed0, g.seed1)
+    f = truth(kind, x, g.alpha).astype(bool)
+    assert 0.3 < f.mean() < 0.7
+
+    def chi2_uniform_bytes(values):
+        counts = np.bincount(values, minlength=256).astype(np.float64)
+        expect = counts.sum() / 256.0
+        return float(((counts - expect) ** 2 / expect).sum())
+
+    # 255 degrees of freedom: mean 255, sd 22.6; 420 is beyond 7 sd
+    for j, key in ((0, k0), (1, k1)):
+        share = oracle.eval_(kind, j, n, key, x)
+        for part in (share[f], share[~f]):
+            for byte in range(4):
+                assert chi2_uniform_bytes((part >> (8 * byte)) & 0xFF) < 420, (j, byte)
+        # the top bit of the share does not follow f(x)
+        top = (share >> 31).astype(np.float64)
+        assert abs(top[f].mean() - top[~f].mean()) < 0.03
+    planes = oracle.split_key(kind, n, batch, k0)
+    s_cw = planes["s_cw"][:, :batch].reshape(-1, 16)
+    assert (s_cw[:, 0] & 1 == 0).all()                        # the control-bit position of a seed-sized word is unused
+    assert chi2_uniform_bytes(s_cw[:, 1:].reshape(-1)[:: 7]) < 420
+    assert chi2_uniform_bytes(s_cw[:, 0] >> 1 << 1 | (s_cw[:, 1] & 1)) < 420
+    assert chi2_uniform_bytes(planes["last"][:batch] & 0xFF) < 420
+    if kind == "cmp":
+        assert chi2_uniform_bytes(planes["leaf"][:, :batch].reshape(-1) >> 24) < 420
+        assert chi2_uniform_bytes(planes["sigma_cw"][:, :batch].reshape(-1) & 0xFF) < 420
+
+
+# ---------------------------------------------------------------- which PRG block feeds what
+
+def replay_walk(n, planes, e, party, x, trace):
+    """Algorithm 4 replayed in Python from the key planes and oracle.prg (itself pinned to OpenSSL's
+    AES in test_oracle_aes): True iff every state of `trace` is what the chosen layout of the
+    PRG output prescribes (child b from block 1 + b, sigma/tau from block 3: words 0 and 1 and the
+    two low bits of byte 8)."""
+    mask = W.ring_mask(n)
+    s = bytes(planes["seed"][e])
+    s = bytes([s[0] & 0xFE]) + s[1:]
+    t = party
+    for i in range(1, n + 1):
+        b = (x >> (n - i)) & 1
+        child = bytearray(oracle.prg(1 + b, s))
+        t_child = child[0] & 1
+        child[0] &= 0xFE
+        wide = oracle.prg(3, s)
+        sigma = int.from_bytes(wide[4 * b:4 * b + 4], "little") & mask
+        tau = (wide[8] >> b) & 1
+        if t:
+            child = bytearray(a ^ c for a, c in zip(child, bytes(planes["s_cw"][i - 1, e])))
+            sigma ^= int(planes["sigma_cw"][i - 1, e])
+            tau ^= (int(planes["ctrl"][e, 2 + b]) >> (i - 1)) & 1
+            t_child ^= (int(planes["ctrl"][e, b]) >> (i - 1)) & 1
+        if bytes(child) != bytes(trace["s"][i]) or t_child != trace["t"][i] or sigma != trace["sigma"][i] or tau != trace["tau"][i]:
+            return False
+        s, t = bytes(child), t_child
+    return True
+
+
+def walk_uses_the_documented_blocks(n=16, batch=12, seed=515):
+    rng = np.random.default_rng(seed)
+    g = W.gen_inputs(rng, n, batch)
+    keys = oracle.gen("cmp", n, g.alpha, g.r, g.seed0, g.seed1)
+    for j in (0, 1):
+        planes = oracle.split_key("cmp", n, batch, keys[j])
+        for e in range(batch):
+            x = int(g.alpha[e]) ^ (1 << int(rng.integers(0, n))) if e % 2 else int(g.alpha[e])
+            if not replay_walk(n, planes, e, j, x, oracle.eval_trace("cmp", j, n, batch, keys[j], e, x)):
+                return False
+    return True
+
+
+def test_walk_uses_the_documented_blocks():
+    assert walk_uses_the_documented_blocks()

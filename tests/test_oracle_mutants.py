@@ -55,6 +55,10 @@ MUTANTS = [
      "rows[out++] = x_share[(c * (size_t)h + (size_t)(oy + dy)) * (size_t)w + (size_t)(ox + dx)];", "argmax"),
     ("eq_mask_drops_alpha", "masked[e] = (le32(k.alpha_share + 4 * e) + y_share[e]) & mask;",
      "masked[e] = y_share[e] & mask;", "eqshared"),
+    ("sigma_tau_block_under_key_1", "oracle_prg(3, seed, w);", "oracle_prg(1, seed, w);", "layout"),
+    ("sigma_words_swapped", "e->sigma[L] = le32(w + 0) & ring_mask(n);\n        e->sigma[R] = le32(w + 4) & ring_mask(n);",
+     "e->sigma[L] = le32(w + 4) & ring_mask(n);\n        e->sigma[R] = le32(w + 0) & ring_mask(n);", "layout"),
+    ("children_under_swapped_keys", "oracle_prg(1 + b, seed, blk);", "oracle_prg(2 - b, seed, blk);", "layout"),
     ("sign_mask_subtracts", "masked[e] = (y_share[e] + le32(k.alpha_share + 4 * e)) & mask;",
      "masked[e] = (y_share[e] - le32(k.alpha_share + 4 * e)) & mask;", "relu"),
 ]
@@ -151,6 +155,8 @@ def test_unmodified_oracle_passes_the_compact_pins():
     assert reconstruction_holds("cmp") and reconstruction_holds("eq")
     assert aes_known_answer_holds() and prg_definition_holds()
     assert relu_identity_holds()
+    from test_oracle_fss import walk_uses_the_documented_blocks
+    assert walk_uses_the_documented_blocks()
 
 
 @pytest.mark.parametrize("name,old,new,pin", MUTANTS, ids=[m[0] for m in MUTANTS])
@@ -160,6 +166,10 @@ def test_planted_mistake_is_caught(tmp_path, monkeypatch, name, old, new, pin):
         assert not aes_known_answer_holds()
     elif pin == "prg":
         assert aes_known_answer_holds() and not prg_definition_holds()
+    elif pin == "layout":
+        # mistakes that still reconstruct (any PRG layout does) but leave the documented one
+        from test_oracle_fss import walk_uses_the_documented_blocks
+        assert reconstruction_holds("cmp") and not walk_uses_the_documented_blocks()
     elif pin == "eqshared":
         assert reconstruction_holds("eq") and not shared_equality_holds()
     elif pin == "argmax":
