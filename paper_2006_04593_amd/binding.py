@@ -129,6 +129,33 @@ def _ptr(t) -> int:
     return 0 if t is None else int(t.data_ptr())
 
 
+def _dev(name: str, t, nbytes: int) -> int:
+    """Address of a device buffer after checking what a raw pointer cannot say: that it is a
+    contiguous GPU tensor of at least `nbytes` bytes.  A kernel launched on a short buffer would
+    fault the GPU; here it is a ValueError instead.  None is let through (the C side rejects NULL
+    unless the call is empty)."""
+    if t is None:
+        return 0
+    if not getattr(t, "is_cuda", False):
+        raise ValueError(f"{name}: expected a GPU tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: tensor is not contiguous")
+    have = t.numel() * t.element_size()
+    if have < nbytes:
+        raise ValueError(f"{name}: {have} bytes, the call needs {nbytes}")
+    return int(t.data_ptr())
+
+
+def _host_pinned(name: str, t, nbytes: int) -> int:
+    if t is None:
+        return 0
+    if getattr(t, "is_cuda", True) or not t.is_pinned():
+        raise ValueError(f"{name}: expected a pinned host tensor")
+    if not t.is_contiguous() or t.numel() * t.element_size() < nbytes:
+        raise ValueError(f"{name}: needs {nbytes} contiguous bytes")
+    return int(t.data_ptr())
+
+
 def _stream(stream) -> int:
     if stream is None:
         import torch
@@ -138,46 +165,55 @@ def _stream(stream) -> int:
     return int(stream.cuda_stream)
 
 
-def _gen(fn, n, batch, d_alpha, d_alpha_r, d_seed0, d_seed1, d_key0, d_key1, stream):
-    _check(fn(n, batch, _ptr(d_alpha), _ptr(d_alpha_r), _ptr(d_seed0), _ptr(d_seed1), _ptr(d_key0), _ptr(d_key1),
-              _stream(stream)))
+def _gen(fn, key_bytes, n, batch, d_alpha, d_alpha_r, d_seed0, d_seed1, d_key0, d_key1, stream):
+    kb = key_bytes(n, batch)
+    _check(fn(n, batch, _dev("alpha", d_alpha, 4 * batch), _dev("alpha_r", d_alpha_r, 4 * batch), _dev("seed0", d_seed0, 16 * batch),
+              _dev("seed1", d_seed1, 16 * batch), _dev("key0", d_key0, kb), _dev("key1", d_key1, kb), _stream(stream)))
 
 
 def cmp_gen(n: int, batch: int, d_alpha, d_alpha_r, d_seed0, d_seed1, d_key0, d_key1, stream=None) -> None:
     """fss_cmp_gen: device tensors in, both parties' key buffers (uint8 device tensors) out."""
-    _gen(lib().fss_cmp_gen, n, batch, d_alpha, d_alpha_r, d_seed0, d_seed1, d_key0, d_key1, stream)
+    _gen(lib().fss_cmp_gen, cmp_key_bytes, n, batch, d_alpha, d_alpha_r, d_seed0, d_seed1, d_key0, d_key1, stream)
 
 
 def eq_gen(n: int, batch: int, d_alpha, d_alpha_r, d_seed0, d_seed1, d_key0, d_key1, stream=None) -> None:
-    _gen(lib().fss_eq_gen, n, batch, d_alpha, d_alpha_r, d_seed0, d_seed1, d_key0, d_key1, stream)
+    _gen(lib().fss_eq_gen, eq_key_bytes, n, batch, d_alpha, d_alpha_r, d_seed0, d_seed1, d_key0, d_key1, stream)
 
 
 def cmp_eval(party: int, n: int, batch: int, d_key, d_x, d_out, stream=None) -> None:
-    _check(lib().fss_cmp_eval(party, n, batch, _ptr(d_key), _ptr(d_x), _ptr(d_out), _stream(stream)))
+    _check(lib().fss_cmp_eval(party, n, batch, _dev("key", d_key, cmp_key_bytes(n, batch)), _dev("x", d_x, 4 * batch),
+                              _dev("out", d_out, 4 * batch), _stream(stream)))
 
 
 def eq_eval(party: int, n: int, batch: int, d_key, d_x, d_out, stream=None) -> None:
-    _check(lib().fss_eq_eval(party, n, batch, _ptr(d_key), _ptr(d_x), _ptr(d_out), _stream(stream)))
+    _check(lib().fss_eq_eval(party, n, batch, _dev("key", d_key, eq_key_bytes(n, batch)), _dev("x", d_x, 4 * batch),
+                             _dev("out", d_out, 4 * batch), _stream(stream)))
 
 
 def sign_mask(n: int, batch: int, d_key, d_y_share, d_masked, stream=None) -> None:
-    _check(lib().fss_sign_mask(n, batch, _ptr(d_key), _ptr(d_y_share), _ptr(d_masked), _stream(stream)))
+    _check(lib().fss_sign_mask(n, batch, _dev("key", d_key, cmp_key_bytes(n, batch)), _dev("y_share", d_y_share, 4 * batch),
+                               _dev("masked", d_masked, 4 * batch), _stream(stream)))
 
 
 def sign_eval(party: int, n: int, batch: int, d_key, d_masked0, d_masked1, d_out, stream=None) -> None:
-    _check(lib().fss_sign_eval(party, n, batch, _ptr(d_key), _ptr(d_masked0), _ptr(d_masked1), _ptr(d_out), _stream(stream)))
+    _check(lib().fss_sign_eval(party, n, batch, _dev("key", d_key, cmp_key_bytes(n, batch)), _dev("masked0", d_masked0, 4 * batch),
+                               _dev("masked1", d_masked1, 4 * batch), _dev("out", d_out, 4 * batch), _stream(stream)))
 
 
 def relu_open(party: int, n: int, batch: int, d_key, d_masked0, d_masked1, d_y_share, d_tri_a, d_tri_b, d_delta, d_eps,
               stream=None) -> None:
-    _check(lib().fss_relu_open(party, n, batch, _ptr(d_key), _ptr(d_masked0), _ptr(d_masked1), _ptr(d_y_share), _ptr(d_tri_a),
-                               _ptr(d_tri_b), _ptr(d_delta), _ptr(d_eps), _stream(stream)))
+    w = 4 * batch
+    _check(lib().fss_relu_open(party, n, batch, _dev("key", d_key, cmp_key_bytes(n, batch)), _dev("masked0", d_masked0, w),
+                               _dev("masked1", d_masked1, w), _dev("y_share", d_y_share, w), _dev("tri_a", d_tri_a, w),
+                               _dev("tri_b", d_tri_b, w), _dev("delta", d_delta, w), _dev("eps", d_eps, w), _stream(stream)))
 
 
 def relu_finish(party: int, n: int, batch: int, d_delta0, d_delta1, d_eps0, d_eps1, d_tri_a, d_tri_b, d_tri_c, d_out,
                 stream=None) -> None:
-    _check(lib().fss_relu_finish(party, n, batch, _ptr(d_delta0), _ptr(d_delta1), _ptr(d_eps0), _ptr(d_eps1), _ptr(d_tri_a),
-                                 _ptr(d_tri_b), _ptr(d_tri_c), _ptr(d_out), _stream(stream)))
+    w = 4 * batch
+    _check(lib().fss_relu_finish(party, n, batch, _dev("delta0", d_delta0, w), _dev("delta1", d_delta1, w), _dev("eps0", d_eps0, w),
+                                 _dev("eps1", d_eps1, w), _dev("tri_a", d_tri_a, w), _dev("tri_b", d_tri_b, w), _dev("tri_c", d_tri_c, w),
+                                 _dev("out", d_out, w), _stream(stream)))
 
 
 def cmp_chunked_key_bytes(n: int, batch: int, chunk: int) -> int:
@@ -187,39 +223,51 @@ def cmp_chunked_key_bytes(n: int, batch: int, chunk: int) -> int:
 def cmp_eval_streamed(party: int, n: int, batch: int, chunk: int, h_key_chunks, d_x, d_out, d_staging, copy_stream,
                       stream=None) -> None:
     """fss_cmp_eval_streamed: h_key_chunks is a pinned HOST tensor in the chunked layout."""
-    _check(lib().fss_cmp_eval_streamed(party, n, batch, chunk, _ptr(h_key_chunks), _ptr(d_x), _ptr(d_out), _ptr(d_staging),
-                                       _stream(copy_stream), _stream(stream)))
+    _check(lib().fss_cmp_eval_streamed(party, n, batch, chunk, _host_pinned("key_chunks", h_key_chunks, cmp_chunked_key_bytes(n, batch, chunk)),
+                                       _dev("x", d_x, 4 * batch), _dev("out", d_out, 4 * batch),
+                                       _dev("staging", d_staging, 2 * cmp_key_bytes(n, chunk)), _stream(copy_stream), _stream(stream)))
 
 
 def eq_mask(n: int, batch: int, d_key, d_y_share, d_masked, stream=None) -> None:
-    _check(lib().fss_eq_mask(n, batch, _ptr(d_key), _ptr(d_y_share), _ptr(d_masked), _stream(stream)))
+    _check(lib().fss_eq_mask(n, batch, _dev("key", d_key, eq_key_bytes(n, batch)), _dev("y_share", d_y_share, 4 * batch),
+                             _dev("masked", d_masked, 4 * batch), _stream(stream)))
 
 
 def eq_masked_eval(party: int, n: int, batch: int, d_key, d_masked0, d_masked1, d_out, stream=None) -> None:
-    _check(lib().fss_eq_masked_eval(party, n, batch, _ptr(d_key), _ptr(d_masked0), _ptr(d_masked1), _ptr(d_out), _stream(stream)))
+    _check(lib().fss_eq_masked_eval(party, n, batch, _dev("key", d_key, eq_key_bytes(n, batch)), _dev("masked0", d_masked0, 4 * batch),
+                                    _dev("masked1", d_masked1, 4 * batch), _dev("out", d_out, 4 * batch), _stream(stream)))
 
 
 def argmax_diff_mask(n: int, rows: int, m: int, d_cmp_key, d_x_share, d_masked, stream=None) -> None:
-    _check(lib().fss_argmax_diff_mask(n, rows, m, _ptr(d_cmp_key), _ptr(d_x_share), _ptr(d_masked), _stream(stream)))
+    pairs = rows * m * (m - 1)
+    _check(lib().fss_argmax_diff_mask(n, rows, m, _dev("cmp_key", d_cmp_key, cmp_key_bytes(n, pairs)), _dev("x_share", d_x_share, 4 * rows * m),
+                                      _dev("masked", d_masked, 4 * pairs), _stream(stream)))
 
 
 def argmax_count_mask(party: int, n: int, rows: int, m: int, d_w_share, d_eq_key, d_masked, stream=None) -> None:
-    _check(lib().fss_argmax_count_mask(party, n, rows, m, _ptr(d_w_share), _ptr(d_eq_key), _ptr(d_masked), _stream(stream)))
+    _check(lib().fss_argmax_count_mask(party, n, rows, m, _dev("w_share", d_w_share, 4 * rows * m * (m - 1)),
+                                       _dev("eq_key", d_eq_key, eq_key_bytes(n, rows * m)), _dev("masked", d_masked, 4 * rows * m),
+                                       _stream(stream)))
 
 
 def maxpool_unroll(channels: int, h: int, w: int, k: int, s: int, d_x_share, d_rows, stream=None) -> None:
-    _check(lib().fss_maxpool_unroll(channels, h, w, k, s, _ptr(d_x_share), _ptr(d_rows), _stream(stream)))
+    windows = ((h - k) // s + 1) * ((w - k) // s + 1) if (s > 0 and h >= k and w >= k) else 0
+    _check(lib().fss_maxpool_unroll(channels, h, w, k, s, _dev("x_share", d_x_share, 4 * channels * h * w),
+                                    _dev("rows", d_rows, 4 * channels * windows * k * k), _stream(stream)))
 
 
 def mul_open(n: int, count: int, d_u_share, d_v_share, d_tri_a, d_tri_b, d_delta, d_eps, stream=None) -> None:
-    _check(lib().fss_mul_open(n, count, _ptr(d_u_share), _ptr(d_v_share), _ptr(d_tri_a), _ptr(d_tri_b), _ptr(d_delta), _ptr(d_eps),
-                              _stream(stream)))
+    w = 4 * count
+    _check(lib().fss_mul_open(n, count, _dev("u_share", d_u_share, w), _dev("v_share", d_v_share, w), _dev("tri_a", d_tri_a, w),
+                              _dev("tri_b", d_tri_b, w), _dev("delta", d_delta, w), _dev("eps", d_eps, w), _stream(stream)))
 
 
 def dot_finish(party: int, n: int, rows: int, m: int, d_delta0, d_delta1, d_eps0, d_eps1, d_tri_a, d_tri_b, d_tri_c, d_out,
                stream=None) -> None:
-    _check(lib().fss_dot_finish(party, n, rows, m, _ptr(d_delta0), _ptr(d_delta1), _ptr(d_eps0), _ptr(d_eps1), _ptr(d_tri_a),
-                                _ptr(d_tri_b), _ptr(d_tri_c), _ptr(d_out), _stream(stream)))
+    w = 4 * rows * m
+    _check(lib().fss_dot_finish(party, n, rows, m, _dev("delta0", d_delta0, w), _dev("delta1", d_delta1, w), _dev("eps0", d_eps0, w),
+                                _dev("eps1", d_eps1, w), _dev("tri_a", d_tri_a, w), _dev("tri_b", d_tri_b, w), _dev("tri_c", d_tri_c, w),
+                                _dev("out", d_out, 4 * rows), _stream(stream)))
 
 
 def quad_layout_below() -> int:

@@ -139,6 +139,13 @@ def test_strerror(lib):
         assert len(lib.fss_strerror(code)) > 0
 
 
+def test_binding_wants_gpu_tensors():
+    torch = pytest.importorskip("torch")
+    t = torch.zeros(8, dtype=torch.int32)
+    with pytest.raises(ValueError, match="GPU tensor"):
+        fss.cmp_eval(0, 32, 8, torch.zeros(fss.cmp_key_bytes(32, 8), dtype=torch.uint8), t, t, stream=0)
+
+
 def test_binding_raises_with_the_code():
     with pytest.raises(fss.FssError) as e:
         fss.cmp_eval(5, 32, 4, None, None, None, stream=0)

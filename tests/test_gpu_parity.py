@@ -226,6 +226,25 @@ def test_empty_batch_is_a_noop_and_errors_raise():
     torch.cuda.synchronize()
 
 
+def test_binding_rejects_buffers_that_are_too_short_or_not_on_the_gpu():
+    n, batch = 32, 1000
+    i32 = lambda count: torch.zeros(count, dtype=torch.int32, device=dev())
+    key = torch.zeros(fss.cmp_key_bytes(n, batch), dtype=torch.uint8, device=dev())
+    with pytest.raises(ValueError, match="out"):
+        fss.cmp_eval(0, n, batch, key, i32(batch), i32(batch - 1))
+    with pytest.raises(ValueError, match="key"):
+        fss.cmp_eval(0, n, batch, key[:-64], i32(batch), i32(batch))
+    with pytest.raises(ValueError, match="GPU tensor"):
+        fss.cmp_eval(0, n, batch, key, torch.zeros(batch, dtype=torch.int32), i32(batch))
+    with pytest.raises(ValueError, match="contiguous"):
+        fss.cmp_eval(0, n, batch, key, i32(2 * batch)[::2], i32(batch))
+    with pytest.raises(ValueError, match="seed1"):
+        fss.cmp_gen(n, batch, i32(batch), i32(batch), torch.zeros((batch, 16), dtype=torch.uint8, device=dev()),
+                    torch.zeros((batch, 8), dtype=torch.uint8, device=dev()), key, torch.zeros_like(key))
+    with pytest.raises(ValueError, match="masked"):
+        fss.argmax_diff_mask(n, 10, 3, torch.zeros(fss.cmp_key_bytes(n, 60), dtype=torch.uint8, device=dev()), i32(30), i32(59))
+
+
 def test_non_default_stream():
     n, batch = 32, 2048
     w = W.uniform_workload("eq", n, batch, seed=31)
