@@ -6,7 +6,9 @@
 //      issue rate of the vector-ALU instructions both engines are made of;
 //   4. the LDS-table engine in its four-lanes-per-block layout (aes_quad.h);
 //   5. whether the vector-memory path could carry some of the lookups beside the LDS (gathers
-//      from a 1-KiB table that stays in the L1 cache).
+//      from a 1-KiB table that stays in the L1 cache);
+//   6. whether the ALU-only engine, launched on a second stream, finds unused vector-ALU cycles
+//      beside the LDS-table engine on the same CUs (its workgroups need no LDS, so they fit).
 // All figures come from HIP events around long launches that fill every CU.
 //
 // usage: aes_engine_bench            (prints a table; exit status 0)
@@ -48,6 +50,25 @@ __global__ __launch_bounds__(kThreads) void lds_engine(uint32_t *out, int iters)
         for (int c = 0; c < 4; c++) s[c] = g[0][c] ^ g[1][(c + 1) & 3];
     }
     out[blockIdx.x * blockDim.x + threadIdx.x] = s[0] ^ s[1] ^ s[2] ^ s[3];
+}
+
+// ---- engine 2 in small workgroups (256 threads, no LDS), to run beside engine 1 on the same CU
+__global__ __launch_bounds__(256) void bitplane_engine_small(uint32_t *out, int iters)
+{
+    bp::W a[8][4];
+    for (int j = 0; j < 8; j++)
+        for (int c = 0; c < 4; c++) a[j][c] = threadIdx.x * 2654435761u + blockIdx.x * 40503u + j * 97u + c;
+    const bp::W pick = ((threadIdx.x * 0x9e3779b9u) >> 24) * 0x01010101u;
+    for (int it = 0; it < iters; it++) {
+        bp::W o[8][4];
+        bp::mmo8<bp::kPickLowK3High>(o, a, pick);
+        for (int j = 0; j < 8; j++)
+            for (int c = 0; c < 4; c++) a[j][c] = o[j][c];
+    }
+    uint32_t r = 0;
+    for (int j = 0; j < 8; j++)
+        for (int c = 0; c < 4; c++) r ^= a[j][c];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = r;
 }
 
 // ---- engine 1 in the quad layout: two chained blocks per quad per iteration
@@ -299,6 +320,43 @@ int main()
                    lookups / (ms * 1e-3) / cus / (ghz * 1e9), lookups * gs[i] / 16 / (ms * 1e-3) / cus / (ghz * 1e9));
         }
         CK(hipFree(table));
+    }
+
+    printf("\nboth engines at once: LDS-table engine on one stream, bit-plane engine (4 workgroups of 256 threads per CU) on another\n");
+    {
+        uint32_t *out2;
+        CK(hipMalloc(&out2, (size_t)cus * 4 * 256 * 4));
+        hipStream_t sa, sb;
+        CK(hipStreamCreate(&sa));
+        CK(hipStreamCreate(&sb));
+        hipEvent_t a0, a1, b1;
+        CK(hipEventCreate(&a0));
+        CK(hipEventCreate(&a1));
+        CK(hipEventCreate(&b1));
+        const int it_lds = 2000;
+        const int bp_iters[3] = { 0, 60, 120 };      // none; about half; about all of the other kernel's duration
+        for (int i = 0; i < 3; i++) {
+            float best = 1e30f;
+            for (int rep = 0; rep < 3; rep++) {
+                CK(hipDeviceSynchronize());
+                CK(hipEventRecord(a0, sa));
+                hipLaunchKernelGGL(lds_engine, dim3(cus), dim3(kThreads), kLdsBytes, sa, out, it_lds);
+                if (bp_iters[i]) hipLaunchKernelGGL(bitplane_engine_small, dim3(cus * 4), dim3(256), 0, sb, out2, bp_iters[i]);
+                CK(hipEventRecord(a1, sa));
+                CK(hipEventRecord(b1, sb));
+                CK(hipDeviceSynchronize());
+                CK(hipGetLastError());
+                float ta, tb;
+                CK(hipEventElapsedTime(&ta, a0, a1));
+                CK(hipEventElapsedTime(&tb, a0, b1));
+                const float span = ta > tb ? ta : tb;
+                if (span < best) best = span;
+            }
+            const double b_lds = (double)cus * kThreads * it_lds * 2, b_bp = (double)cus * 4 * 256 * bp_iters[i] * 8;
+            printf("  bit-plane iterations %3d  %8.3f ms  %6.1f G + %5.1f G = %6.1f G blocks/s\n", bp_iters[i], best, b_lds / best / 1e6,
+                   b_bp / best / 1e6, (b_lds + b_bp) / best / 1e6);
+        }
+        CK(hipFree(out2));
     }
     CK(hipFree(out));
     return 0;
