@@ -211,7 +211,7 @@ int fss_cmp_eval_streamed(int party, int n, size_t batch, size_t chunk, const vo
  * lanes per element (a quarter of the dependent work per wavefront and four times the wavefronts:
  * lower latency while a batch is too small to fill the device).  The entry points pick by batch
  * size.  fss_quad_layout_below() returns the batch size below which the current device uses the
- * four-lane layout (device-dependent: 448 elements per compute unit), or 0 if the device cannot
+ * four-lane layout (device-dependent: 512 elements per compute unit), or 0 if the device cannot
  * be queried. */
 size_t fss_quad_layout_below(void);
 

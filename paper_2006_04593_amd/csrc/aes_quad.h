@@ -108,7 +108,9 @@ __device__ __forceinline__ void aes_mmo_quad(uint32_t (&out)[sizeof...(M)], cons
         }
         const uint32_t v1 = quad_perm<kQuadRot1>(v[1]), v2 = quad_perm<kQuadRot2>(v[2]), v3 = quad_perm<kQuadRot3>(v[3]);
         if (r < 10) {
-            st[b] = (v[0] ^ v1) ^ (v2 ^ v3) ^ round_key(b, r);
+            // two independent pairs, then one three-way XOR: no DPP operand waits for a result that a
+            // vector instruction has just written (the chain v0 ^ v1 ^ v2 ^ v3 costs two idle cycles per link)
+            st[b] = bitop3<kXor3>(v[0] ^ v1, v2 ^ v3, round_key(b, r));
         } else {
             // last round: SubBytes + ShiftRows only, S(x) = byte r of the row-r lookup
             const uint32_t lo = __builtin_amdgcn_perm(v1, v[0], 0x0c0c0500u);

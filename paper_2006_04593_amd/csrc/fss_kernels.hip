@@ -700,9 +700,9 @@ static LaunchShape shape_for(size_t elems, const DeviceInfo &d, size_t tile_elem
 
 // The quad layout (four lanes per element) serves batches that would leave the CUs short of
 // wavefronts with one lane per element.  Measured on MI355X, for KeyGen and Eval, comparison and
-// equality alike: the quad layout is faster below about 7 wavefronts of 64 elements per CU (2.7x
-// for Eval and 2x for KeyGen at 16,384 elements), slower above (by 25-30 % on large batches).
-constexpr size_t kQuadBelowWavesPerCu = 7;
+// equality alike: the quad layout is faster below about 8 wavefronts of 64 elements per CU (2.1x
+// for Eval and 2.2x for KeyGen at 16,384 elements), slower above (by 25-30 % on large batches).
+constexpr size_t kQuadBelowWavesPerCu = 8;
 
 static size_t quad_layout_below(const DeviceInfo &d) { return (size_t)d.cus * 64 * kQuadBelowWavesPerCu; }
 

@@ -129,8 +129,8 @@ def test_streamed_evaluation_arguments(lib):
 
 
 def test_layout_switch_query(lib):
-    # 448 elements per compute unit on a device; 0 where there is none to ask
-    assert lib.fss_quad_layout_below() % (64 * 7) == 0
+    # 512 elements per compute unit on a device; 0 where there is none to ask
+    assert lib.fss_quad_layout_below() % 512 == 0
 
 
 def test_strerror(lib):
