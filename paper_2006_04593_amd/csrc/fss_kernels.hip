@@ -681,20 +681,17 @@ struct LaunchShape {
     unsigned grid, threads;
 };
 
-// One workgroup per CU (its tables take 128 KiB of the CU's LDS); the kernels loop over tiles of
-// 64 elements (16 in the quad layout).  Every CU gets a workgroup as soon as there are that many
-// tiles, with just enough wavefronts to cover its share (16 at most).
+// One workgroup per CU (its tables take 128 KiB of the CU's LDS), always of 16 wavefronts: the
+// kernels loop over tiles of 64 elements (16 in the quad layout), and wavefronts that get no tile
+// still help to fill the tables (2-3 us of a small launch).  Every CU gets a workgroup as soon as
+// there are that many tiles.
 static LaunchShape shape_for(size_t elems, const DeviceInfo &d, size_t tile_elems = 64)
 {
     const size_t cus = (size_t)d.cus;
     const size_t tiles = (elems + tile_elems - 1) / tile_elems;
-    const size_t groups = tiles < cus ? tiles : cus;
-    size_t waves = (tiles + groups - 1) / groups;
-    if (waves > (size_t)kThreads / 64) waves = kThreads / 64;
-    if (waves < 4) waves = 4;       // wavefronts without a tile still help to fill the tables
     LaunchShape s;
-    s.threads = (unsigned)(waves * 64);
-    s.grid = (unsigned)groups;
+    s.threads = (unsigned)kThreads;
+    s.grid = (unsigned)(tiles < cus ? tiles : cus);
     return s;
 }
 
