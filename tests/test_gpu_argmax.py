@@ -88,9 +88,15 @@ def same(a, b, names):
             assert np.array_equal(np.asarray(a[name][j]).reshape(-1), np.asarray(b[name][j]).reshape(-1)), (name, j)
 
 
-# the last case is large enough for both evaluations (921,600 comparisons, 115,200 equalities) to run one lane per element
-@pytest.mark.parametrize("n,rows,m", [(32, 1, 2), (32, 100, 10), (16, 257, 4), (32, 64, 9), (12, 31, 3), (32, 12800, 9)])
+# rows = None: sized from the library's switch of register layouts so that BOTH evaluations of the
+# flow -- the m(m-1) comparisons per row and the m equalities per row -- run one lane per element;
+# (32, 12800, 9) has 921,600 comparisons in that layout and 115,200 equalities four lanes per element
+@pytest.mark.parametrize("n,rows,m", [(32, 1, 2), (32, 100, 10), (16, 257, 4), (32, 64, 9), (12, 31, 3), (32, 12800, 9), (32, None, 4)])
 def test_argmax_matches_oracle(n, rows, m):
+    if rows is None:
+        switch = fss.quad_layout_below()
+        rows = switch // m + 64
+        assert rows * m >= switch and rows * m * (m - 1) >= switch
     print(f"case argmax n={n} rows={rows} m={m}", flush=True)
     rng = np.random.default_rng(n * 100 + rows + m)
     x = W.fixed_point_normal(rng, (rows, m), frac_bits=max(1, min(10, n - 14)))

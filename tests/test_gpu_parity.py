@@ -70,7 +70,8 @@ def check_full(kind, n, g: W.GenInputs, x: np.ndarray):
 # sizes: below one wavefront, ragged tails, several 1024-element workgroup tiles
 @pytest.mark.parametrize("kind", ["cmp", "eq"])
 @pytest.mark.parametrize("n,batch", [(32, 1), (32, 63), (32, 64), (32, 65), (32, 1000), (32, 1024), (32, 5000),
-                                     (32, 16384), (1, 100), (2, 129), (8, 300), (12, 2049), (16, 4097), (31, 777)])
+                                     (32, 16384), (1, 100), (2, 129), (8, 300), (12, 2049), (16, 4097), (31, 777),
+                                     (24, 5000), (28, 4097)])
 def test_gen_and_eval_match_oracle(kind, n, batch):
     w = W.uniform_workload(kind, n, batch, seed=1000 * n + batch)
     x = w.x.copy()
@@ -84,7 +85,8 @@ def test_gen_and_eval_match_oracle(kind, n, batch):
 # fss.quad_layout_below() elements, one lane per element from there on).  The sizes above all
 # fall into the first; these straddle the switch, with ragged tails on both sides.
 @pytest.mark.parametrize("kind", ["cmp", "eq"])
-@pytest.mark.parametrize("n,offset", [(32, -17), (32, -1), (32, 0), (32, 1), (32, 63), (32, 65), (12, 1000), (8, 129), (1, 3)])
+@pytest.mark.parametrize("n,offset", [(32, -17), (32, -1), (32, 0), (32, 1), (32, 63), (32, 65), (12, 1000), (8, 129), (1, 3),
+                                      (24, -3), (24, 71), (28, -64), (28, 200), (16, 1)])
 def test_both_layouts_around_the_switch(kind, n, offset):
     switch = fss.quad_layout_below()
     assert switch > 0 and switch % 64 == 0
@@ -270,7 +272,7 @@ def test_non_default_stream():
 def check_sampled(kind, n, g: W.GenInputs, x: np.ndarray, samples: int, seed: int):
     """Full-size run on the GPU; the oracle recomputes a seeded sample of elements (keys of
     an element depend on that element's arguments only) and the reconstruction identity is
-    checked on every element."""
+    checked on every element.  Only for batches the oracle cannot walk in a test's time."""
     print(f"case kind={kind} n={n} batch={g.batch} sampled={samples}", flush=True)
     k0, k1 = gpu_gen(kind, n, g)
     o0, o1 = gpu_eval(kind, 0, n, k0, x), gpu_eval(kind, 1, n, k1, x)
@@ -294,6 +296,45 @@ def check_sampled(kind, n, g: W.GenInputs, x: np.ndarray, samples: int, seed: in
     return o0, o1
 
 
+ELEMENT_PLANES = ("alpha_share", "seed", "ctrl", "last")          # [Bp, ...]
+LEVEL_PLANES = {"cmp": ("s_cw", "sigma_cw", "leaf"), "eq": ("s_cw",)}   # [n, Bp, ...]
+
+
+def compare_with_oracle_in_chunks(kind, n, g: W.GenInputs, x, keys, shares, chunk=1 << 20):
+    """EVERY element of a full-size GPU run against the oracle: all planes of both key buffers byte
+    for byte and both parties' shares.  An element's key depends on that element's arguments only,
+    so the oracle walks the batch in chunks of `chunk` elements (bounded host memory) and each
+    chunk's planes are compared with the matching slice of the GPU's planes; padding elements of
+    the GPU buffers must be zero."""
+    batch = g.batch
+    host = [oracle.split_key(kind, n, batch, k.cpu().numpy()) for k in keys]
+    for c0 in range(0, batch, chunk):
+        c1 = min(c0 + chunk, batch)
+        r = oracle.gen(kind, n, g.alpha[c0:c1], g.r[c0:c1], g.seed0[c0:c1], g.seed1[c0:c1])
+        for j in (0, 1):
+            part = oracle.split_key(kind, n, c1 - c0, r[j])
+            for plane in ELEMENT_PLANES:
+                assert np.array_equal(host[j][plane][c0:c1], part[plane][:c1 - c0]), (plane, j, c0)
+            for plane in LEVEL_PLANES[kind]:
+                assert np.array_equal(host[j][plane][:, c0:c1], part[plane][:, :c1 - c0]), (plane, j, c0)
+            assert np.array_equal(shares[j][c0:c1], oracle.eval_(kind, j, n, r[j], x[c0:c1])), ("share", j, c0)
+        print(f"  elements [{c0}, {c1}) match the oracle", flush=True)
+    for j in (0, 1):
+        for plane in ELEMENT_PLANES:
+            assert not host[j][plane][batch:].any(), (plane, "padding")
+        for plane in LEVEL_PLANES[kind]:
+            assert not host[j][plane][:, batch:].any(), (plane, "padding")
+
+
+def check_every_element(kind, n, g: W.GenInputs, x: np.ndarray):
+    print(f"case kind={kind} n={n} batch={g.batch} every element", flush=True)
+    k0, k1 = gpu_gen(kind, n, g)
+    o0, o1 = gpu_eval(kind, 0, n, k0, x), gpu_eval(kind, 1, n, k1, x)
+    assert np.array_equal((o0 + o1) & np.uint32(W.ring_mask(n)), truth(kind, x, g.alpha))
+    compare_with_oracle_in_chunks(kind, n, g, x, (k0, k1), (o0, o1))
+    return o0, o1
+
+
 def test_config1_comparison_16k():
     w = W.config_workload(1)
     check_full("cmp", 32, w.gen, w.x)
@@ -301,48 +342,48 @@ def test_config1_comparison_16k():
 
 def test_config2_equality_1m():
     w = W.config_workload(2)
-    o0, o1 = check_sampled("eq", 32, w.gen, w.x, samples=4096, seed=2)
+    o0, o1 = check_every_element("eq", 32, w.gen, w.x)
     assert np.array_equal((o0 + o1).astype(bool), w.extra["hit"] | (w.x == w.gen.alpha))
 
 
 def test_config3_relu_layer():
     w = W.config_workload(3)
-    o0, o1 = check_sampled("cmp", 32, w.gen, w.x, samples=4096, seed=3)
+    o0, o1 = check_every_element("cmp", 32, w.gen, w.x)
     # Sign protocol: disagrees with 1{y <= 0} only on the rare wrap-around (|y| / 2^32 each)
     assert ((o0 + o1) != (w.extra["y"] <= 0)).sum() <= 8
 
 
 def test_config4_maxpool_dependent_rounds():
     """8 dependent comparison rounds of 200,704 elements: running maximum over the nine
-    taps of each 3x3 window; the reveal between rounds is done in the clear by the test."""
+    taps of each 3x3 window; the reveal between rounds is done in the clear by the test.
+    Every key byte and every share of every round is compared with the oracle."""
     n = 32
     taps = W.maxpool_taps(W.BASE_SEED + 4)
     batch = taps.shape[1]
     assert batch == 64 * 56 * 56
     m = taps[0].copy()
-    rng = np.random.default_rng(44)
-    idx = np.sort(rng.choice(batch, size=1024, replace=False))
     for rnd in range(1, W.MAXPOOL_ROUNDS + 1):
         g = W.maxpool_round_keys(W.BASE_SEED + 4, rnd, batch)
         d = m - taps[rnd]                                   # m <= w  <=>  d <= 0
         x = ((d + g.alpha.astype(np.int64)) & 0xFFFFFFFF).astype(np.uint32)
-        k0, k1 = gpu_gen("cmp", n, g)
-        o0, o1 = gpu_eval("cmp", 0, n, k0, x), gpu_eval("cmp", 1, n, k1, x)
-        c = o0 + o1
-        assert np.array_equal(c, truth("cmp", x, g.alpha))
-        sub = W.GenInputs(n=n, alpha=g.alpha[idx], r=g.r[idx], seed0=g.seed0[idx], seed1=g.seed1[idx])
-        r0, r1 = oracle.gen("cmp", n, sub.alpha, sub.r, sub.seed0, sub.seed1)
-        assert np.array_equal(o0[idx], oracle.eval_("cmp", 0, n, r0, x[idx]))
-        assert np.array_equal(o1[idx], oracle.eval_("cmp", 1, n, r1, x[idx]))
-        m = np.where(c == 1, taps[rnd], m)
-        del k0, k1
+        print(f"round {rnd}", flush=True)
+        o0, o1 = check_every_element("cmp", n, g, x)
+        m = np.where((o0 + o1) == 1, taps[rnd], m)
     # wrap-around failures are ~|d|/2^32 per comparison: allow a handful of windows to differ
     assert (m != taps.max(axis=0)).sum() <= 8
 
 
-def test_config5_large_batch_sampled():
+def test_config5_large_batch():
+    """2^22 elements, the benchmark's launch (16 passes of the one-lane-per-element kernels):
+    every key byte and share against the oracle."""
     w = W.config_workload(5)
-    check_sampled("cmp", 32, w.gen, w.x, samples=8192, seed=5)
+    check_every_element("cmp", 32, w.gen, w.x)
+
+
+def test_small_ring_large_batch_every_element():
+    """n = 16 at 2^20 elements: the multi-pass loop of the one-lane-per-element kernels on a short ring."""
+    w = W.uniform_workload("cmp", 16, 1 << 20, seed=1620)
+    check_every_element("cmp", 16, w.gen, w.x)
 
 
 def test_key_buffer_beyond_4_gib():

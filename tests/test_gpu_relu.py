@@ -68,7 +68,7 @@ def oracle_relu_layer(n, g, ri, idx=None):
     return dict(masked=masked, sign=sign, delta=[op[0][0], op[1][0]], eps=[op[0][1], op[1][1]], z=z)
 
 
-@pytest.mark.parametrize("n,batch", [(32, 1), (32, 777), (32, 4096), (12, 4096), (8, 256), (16, 1000)])
+@pytest.mark.parametrize("n,batch", [(32, 1), (32, 777), (32, 4096), (12, 4096), (8, 256), (16, 1000), (24, 3000), (28, 1025)])
 def test_relu_layer_matches_oracle(n, batch):
     print(f"case relu n={n} batch={batch}", flush=True)
     rng = np.random.default_rng(n * 1000 + batch)
@@ -91,9 +91,11 @@ def test_relu_layer_matches_oracle(n, batch):
 
 
 def test_relu_layer_config3_shape():
-    """64 x 112 x 112 activations: the fused round at the benchmark size; the oracle recomputes a
-    seeded sample, the ReLU identity is checked on every element."""
+    """64 x 112 x 112 activations: the fused round at the benchmark size (one lane per element,
+    ragged last pass).  Every intermediate of both parties on EVERY element against the oracle,
+    and the ReLU identity."""
     n, batch = 32, 64 * 112 * 112
+    print(f"case relu layer n={n} batch={batch} every element", flush=True)
     rng = np.random.default_rng(W.BASE_SEED + 3)
     y = W.fixed_point_normal(rng, batch)
     g = W.gen_inputs(rng, n, batch)
@@ -104,12 +106,10 @@ def test_relu_layer_config3_shape():
     assert fail.sum() <= 8                                    # Sign wrap-around, |y| / 2^32 each
     want = (np.maximum(y, 0) & 0xFFFFFFFF).astype(np.uint32)
     assert np.array_equal(rec[~fail], want[~fail])
-    idx = np.sort(np.random.default_rng(33).choice(batch, size=4096, replace=False))
-    idx[0], idx[-1] = 0, batch - 1
-    ref = oracle_relu_layer(n, g, ri, idx)
+    ref = oracle_relu_layer(n, g, ri)
     for name in ("masked", "sign", "delta", "eps", "z"):
         for j in (0, 1):
-            assert np.array_equal(got[name][j][idx], ref[name][j]), (name, j)
+            assert np.array_equal(got[name][j], ref[name][j]), (name, j)
 
 
 def test_bad_arguments():

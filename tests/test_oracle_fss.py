@@ -322,7 +322,9 @@ def replay_walk(n, planes, e, party, x, trace):
     """Algorithm 4 replayed in Python from the key planes and oracle.prg (itself pinned to OpenSSL's
     AES in test_oracle_aes): True iff every state of `trace` is what the chosen layout of the
     PRG output prescribes (child b from block 1 + b, sigma/tau from block 3: words 0 and 1 and the
-    two low bits of byte 8)."""
+    two low bits of byte 8), every out_i including the final term of the return line (which word of
+    the last seed is read as a ring element), and the share is their signed sum.  The paper prints
+    none of these positions: this pins the DOCUMENTED reading, which reconstruction cannot see."""
     mask = W.ring_mask(n)
     s = bytes(planes["seed"][e])
     s = bytes([s[0] & 0xFE]) + s[1:]
@@ -342,20 +344,44 @@ def replay_walk(n, planes, e, party, x, trace):
             t_child ^= (int(planes["ctrl"][e, b]) >> (i - 1)) & 1
         if bytes(child) != bytes(trace["s"][i]) or t_child != trace["t"][i] or sigma != trace["sigma"][i] or tau != trace["tau"][i]:
             return False
+        # out_i = tau . CW_leaf^(i) + sigma (the party's sign is applied to the sum at the end)
+        if int(trace["out"][i]) != ((int(planes["leaf"][i - 1, e]) if tau else 0) + sigma) & mask:
+            return False
         s, t = bytes(child), t_child
-    return True
+    # out_{n+1} = t . CW^(n+1) + conv(s): the ring element read from the final seed is the little-endian
+    # word in bytes 12..15, reduced mod 2^n
+    conv = int.from_bytes(s[12:16], "little") & mask
+    if int(trace["out"][n + 1]) != ((int(planes["last"][e]) if t else 0) + conv) & mask:
+        return False
+    total = sum(int(v) for v in trace["out"][1:n + 2]) & mask
+    return trace["share"] == (total if party == 0 else (-total) & mask)
+
+
+def final_correction_word_follows_algorithm_3(n, planes0, planes1, e, trace0, trace1):
+    """Last assignment of KeyGen: CW^(n+1) = (-1)^{t_1} (1 - conv(s_0) + conv(s_1)) over the two
+    parties' final states ON the special path (traces of x = alpha), conv as in replay_walk."""
+    mask = W.ring_mask(n)
+    c0 = int.from_bytes(bytes(trace0["s"][n][12:16]), "little") & mask
+    c1 = int.from_bytes(bytes(trace1["s"][n][12:16]), "little") & mask
+    want = (1 - c0 + c1) & mask
+    if trace1["t"][n]:
+        want = (-want) & mask
+    return int(planes0["last"][e]) == want and int(planes1["last"][e]) == want
 
 
 def walk_uses_the_documented_blocks(n=16, batch=12, seed=515):
     rng = np.random.default_rng(seed)
     g = W.gen_inputs(rng, n, batch)
     keys = oracle.gen("cmp", n, g.alpha, g.r, g.seed0, g.seed1)
-    for j in (0, 1):
-        planes = oracle.split_key("cmp", n, batch, keys[j])
-        for e in range(batch):
-            x = int(g.alpha[e]) ^ (1 << int(rng.integers(0, n))) if e % 2 else int(g.alpha[e])
-            if not replay_walk(n, planes, e, j, x, oracle.eval_trace("cmp", j, n, batch, keys[j], e, x)):
+    planes = [oracle.split_key("cmp", n, batch, keys[j]) for j in (0, 1)]
+    for e in range(batch):
+        x = int(g.alpha[e]) ^ (1 << int(rng.integers(0, n))) if e % 2 else int(g.alpha[e])
+        traces = [oracle.eval_trace("cmp", j, n, batch, keys[j], e, x) for j in (0, 1)]
+        for j in (0, 1):
+            if not replay_walk(n, planes[j], e, j, x, traces[j]):
                 return False
+        if x == int(g.alpha[e]) and not final_correction_word_follows_algorithm_3(n, planes[0], planes[1], e, traces[0], traces[1]):
+            return False
     return True
 
 

@@ -59,6 +59,10 @@ MUTANTS = [
     ("sigma_words_swapped", "e->sigma[L] = le32(w + 0) & ring_mask(n);\n        e->sigma[R] = le32(w + 4) & ring_mask(n);",
      "e->sigma[L] = le32(w + 4) & ring_mask(n);\n        e->sigma[R] = le32(w + 0) & ring_mask(n);", "layout"),
     ("children_under_swapped_keys", "oracle_prg(1 + b, seed, blk);", "oracle_prg(2 - b, seed, blk);", "layout"),
+    ("conv_reads_another_word", "return le32(s + 12) & ring_mask(n); }", "return le32(s + 8) & ring_mask(n); }", "layout"),
+    ("final_cw_from_other_party_bit", "if (t[1]) last = (0u - last) & mask;", "if (t[0]) last = (0u - last) & mask;", "both"),
+    ("final_term_reads_another_plane", "uint32_t out_last = ((t ? le32(k->last + 4 * e) : 0u) + conv(s, n)) & mask;",
+     "uint32_t out_last = ((t ? le32(k->last + 4 * e) : 0u) + (le32(s + 4) & mask)) & mask;", "both"),
     ("sign_mask_subtracts", "masked[e] = (y_share[e] + le32(k.alpha_share + 4 * e)) & mask;",
      "masked[e] = (y_share[e] - le32(k.alpha_share + 4 * e)) & mask;", "relu"),
 ]
