@@ -15,14 +15,22 @@
  * General rules
  *   - Every pointer whose name starts with d_ is DEVICE memory on the current HIP device,
  *     owned by the caller before, during and after the call.  The library allocates no
- *     device memory, keeps no pointer, and holds no state between calls that affects
- *     results (it remembers per device that its kernels were configured).
+ *     device memory and keeps no pointer of the caller.  The only state it holds between
+ *     calls is per device and never affects results: that its kernels were configured, and
+ *     what fss_prepare() describes.
+ *   - The FIRST call on a device configures the kernels (one hipDeviceGetAttribute and one
+ *     hipFuncSetAttribute per kernel).  Those calls are not allowed while a stream is being
+ *     captured into a graph: call fss_prepare() (or any entry point, eagerly) once per device
+ *     before capturing.
  *   - Calls only ENQUEUE work on `stream` (a hipStream_t; NULL = the default stream) and
  *     return without waiting; the caller synchronises.  Buffers must stay valid until the
- *     enqueued work has finished.
+ *     enqueued work has finished.  (The two fss_cmp_eval_streamed* calls block; see there.)
  *   - Return value: FSS_OK (0) or a negative FSS_E* code; nothing aborts or throws.
- *     Arguments are checked on the host before any device work is enqueued, so a failed
- *     call has no effect.  batch == 0 is a successful no-op (pointers may then be NULL).
+ *     Arguments are checked on the host before any device work is enqueued, so a call that
+ *     fails with FSS_EINVAL or FSS_ELIMIT has no effect.  FSS_ELAUNCH comes from the HIP
+ *     runtime; the single-launch entry points have enqueued nothing when they return it, the
+ *     streamed ones may have evaluated the chunks before the failure (d_out partly written).
+ *     batch == 0 is a successful no-op (pointers may then be NULL).
  *   - Values of alpha, r and x are reduced mod 2^n (high bits ignored).
  *   - Alignment: key buffers 256 bytes; seed arrays 16 bytes; u32 arrays 4 bytes.
  *
@@ -83,6 +91,13 @@ typedef void *fss_stream_t; /* hipStream_t */
 #define FSS_EINVAL (-1)   /* party not in {0,1}; n not in [1,32]; more than FSS_MAX_BATCH elements; NULL or misaligned pointer with batch > 0 */
 #define FSS_ELAUNCH (-2)  /* the HIP runtime refused a launch or an attribute; see fss_last_hip_error() */
 #define FSS_EDEVICE (-3)  /* current device cannot run the kernels (needs 128 KiB of LDS per workgroup) */
+#define FSS_ELIMIT (-4)   /* a size is beyond a fixed limit of the entry point (fss_cmp_eval_streamed_static) */
+
+/* Per-device set-up for the CURRENT device, idempotent and thread-safe: configures the kernels
+ * (they need 128 KiB of dynamic LDS).  Every entry point does this by itself on its first call
+ * on a device; calling it explicitly keeps that work out of latency-critical or captured code.
+ * FSS_OK, FSS_EDEVICE (the device cannot run the kernels) or FSS_ELAUNCH. */
+int fss_prepare(void);
 
 /* Size in bytes of ONE party's key buffer for `batch` elements, padding included
  * (808 * Bp for comparison and 544 * Bp for equality at n = 32).  0 if n is out of range or

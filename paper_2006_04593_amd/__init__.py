@@ -24,6 +24,7 @@ from .binding import (  # noqa: F401
     eq_key_bytes,
     lib,
     library_path,
+    prepare,
     quad_layout_below,
     relu_finish,
     relu_open,

@@ -17,7 +17,7 @@ EXPORTS = ("fss_cmp_key_bytes", "fss_eq_key_bytes", "fss_cmp_gen", "fss_cmp_eval
            "fss_sign_mask", "fss_sign_eval", "fss_relu_open", "fss_relu_finish", "fss_eq_mask", "fss_eq_masked_eval",
            "fss_argmax_diff_mask", "fss_argmax_count_mask", "fss_maxpool_unroll", "fss_mul_open", "fss_dot_finish",
            "fss_cmp_chunked_key_bytes",
-           "fss_cmp_eval_streamed", "fss_quad_layout_below", "fss_strerror", "fss_last_hip_error")
+           "fss_cmp_eval_streamed", "fss_prepare", "fss_quad_layout_below", "fss_strerror", "fss_last_hip_error")
 
 HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -101,6 +101,8 @@ def lib() -> C.CDLL:
         L.fss_cmp_chunked_key_bytes.restype = sz
         L.fss_cmp_eval_streamed.argtypes = [i, i, sz, sz, vp, vp, vp, vp, vp, vp]
         L.fss_cmp_eval_streamed.restype = i
+        L.fss_prepare.argtypes = []
+        L.fss_prepare.restype = i
         L.fss_quad_layout_below.argtypes = []
         L.fss_quad_layout_below.restype = sz
         L.fss_strerror.argtypes = [i]
@@ -268,6 +270,11 @@ def dot_finish(party: int, n: int, rows: int, m: int, d_delta0, d_delta1, d_eps0
     _check(lib().fss_dot_finish(party, n, rows, m, _dev("delta0", d_delta0, w), _dev("delta1", d_delta1, w), _dev("eps0", d_eps0, w),
                                 _dev("eps1", d_eps1, w), _dev("tri_a", d_tri_a, w), _dev("tri_b", d_tri_b, w), _dev("tri_c", d_tri_c, w),
                                 _dev("out", d_out, 4 * rows), _stream(stream)))
+
+
+def prepare() -> None:
+    """fss_prepare: per-device set-up of the current device (kernel attributes), once, ahead of the first call."""
+    _check(lib().fss_prepare())
 
 
 def quad_layout_below() -> int:

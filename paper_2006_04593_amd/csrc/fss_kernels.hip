@@ -8,6 +8,7 @@
 #include <stdint.h>
 
 #include <mutex>
+#include <tuple>
 
 #include "../../include/fss.h"
 #include "aes_lds.h"
@@ -705,9 +706,17 @@ static size_t quad_layout_below(const DeviceInfo &d) { return (size_t)d.cus * 64
 
 static bool use_quad_layout(size_t batch, const DeviceInfo &d) { return batch < quad_layout_below(d); }
 
-static int check_launch()
+// Launch through hipLaunchKernel and report ITS return value: the thread's last-error slot (which
+// hipGetLastError would read and clear) may hold an unrelated error of the host application.
+template <typename... P, typename... A>
+static int launch(void (*kernel)(P...), unsigned grid, unsigned threads, size_t lds_bytes, hipStream_t st, A... a)
 {
-    hipError_t err = hipGetLastError();
+    static_assert(sizeof...(P) == sizeof...(A), "one argument per kernel parameter");
+    std::tuple<P...> vals(static_cast<P>(a)...);
+    void *ptrs[sizeof...(P)];
+    size_t i = 0;
+    std::apply([&](auto &...v) { ((ptrs[i++] = static_cast<void *>(&v)), ...); }, vals);
+    const hipError_t err = hipLaunchKernel(reinterpret_cast<const void *>(kernel), dim3(grid), dim3(threads), ptrs, lds_bytes, st);
     if (err != hipSuccess) { g_last_hip_error = (int)err; return FSS_ELAUNCH; }
     return FSS_OK;
 }
@@ -735,14 +744,10 @@ static int gen_common(bool cmp, int n, size_t batch, const uint32_t *d_alpha, co
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (use_quad_layout(batch, dev)) {
         const LaunchShape ls = shape_for(padded_batch(batch), dev, 16);
-        if (cmp) hipLaunchKernelGGL(gen_quad_kernel<true>, dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
-        else hipLaunchKernelGGL(gen_quad_kernel<false>, dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
-        return check_launch();
+        return launch(cmp ? gen_quad_kernel<true> : gen_quad_kernel<false>, ls.grid, ls.threads, kLdsBytes, st, a);
     }
     const LaunchShape ls = shape_for(padded_batch(batch), dev);
-    if (cmp) hipLaunchKernelGGL(gen_kernel<true>, dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
-    else hipLaunchKernelGGL(gen_kernel<false>, dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
-    return check_launch();
+    return launch(cmp ? gen_kernel<true> : gen_kernel<false>, ls.grid, ls.threads, kLdsBytes, st, a);
 }
 
 static int eval_common(bool cmp, int mode, int party, int n, size_t batch, const void *d_key, const uint32_t *d_x,
@@ -765,22 +770,21 @@ static int eval_common(bool cmp, int mode, int party, int n, size_t batch, const
     a.y_share = d_y; a.tri_a = d_ta; a.tri_b = d_tb;
     a.batch = batch; a.n = n; a.party = party;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (use_quad_layout(batch, dev)) {
-        const LaunchShape ls = shape_for(batch, dev, 16);
-        if (!cmp && mode == kPlain) hipLaunchKernelGGL((eval_quad_kernel<false, kPlain>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
-        else if (!cmp) hipLaunchKernelGGL((eval_quad_kernel<false, kSign>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
-        else if (mode == kPlain) hipLaunchKernelGGL((eval_quad_kernel<true, kPlain>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
-        else if (mode == kSign) hipLaunchKernelGGL((eval_quad_kernel<true, kSign>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
-        else hipLaunchKernelGGL((eval_quad_kernel<true, kReluOpen>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
-        return check_launch();
+    const bool quad = use_quad_layout(batch, dev);
+    const LaunchShape ls = shape_for(batch, dev, quad ? 16 : 64);
+    void (*kernel)(EvalArgs);
+    if (quad) {
+        kernel = !cmp ? (mode == kPlain ? eval_quad_kernel<false, kPlain> : eval_quad_kernel<false, kSign>)
+                      : mode == kPlain ? eval_quad_kernel<true, kPlain>
+                      : mode == kSign  ? eval_quad_kernel<true, kSign>
+                                       : eval_quad_kernel<true, kReluOpen>;
+    } else {
+        kernel = !cmp ? (mode == kPlain ? eval_kernel<false, kPlain> : eval_kernel<false, kSign>)
+                      : mode == kPlain ? eval_kernel<true, kPlain>
+                      : mode == kSign  ? eval_kernel<true, kSign>
+                                       : eval_kernel<true, kReluOpen>;
     }
-    const LaunchShape ls = shape_for(batch, dev);
-    if (!cmp && mode == kPlain) hipLaunchKernelGGL((eval_kernel<false, kPlain>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
-    else if (!cmp) hipLaunchKernelGGL((eval_kernel<false, kSign>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
-    else if (mode == kPlain) hipLaunchKernelGGL((eval_kernel<true, kPlain>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
-    else if (mode == kSign) hipLaunchKernelGGL((eval_kernel<true, kSign>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
-    else hipLaunchKernelGGL((eval_kernel<true, kReluOpen>), dim3(ls.grid), dim3(ls.threads), kLdsBytes, st, a);
-    return check_launch();
+    return launch(kernel, ls.grid, ls.threads, kLdsBytes, st, a);
 }
 
 static unsigned elementwise_grid(size_t batch)
@@ -801,9 +805,57 @@ static int mask_common(bool cmp, int n, size_t batch, const void *d_key, const u
     if (batch == 0) return FSS_OK;
     if (!d_key || misaligned(d_key, 256) || bad_u32_ptr(d_y_share) || bad_u32_ptr(d_masked)) return FSS_EINVAL;
     const uint32_t *alpha_share = reinterpret_cast<const uint32_t *>(static_cast<const uint8_t *>(d_key) + key_layout(cmp, n, batch).alpha_share);
-    hipLaunchKernelGGL(sign_mask_kernel, dim3(elementwise_grid(batch)), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       alpha_share, d_y_share, d_masked, batch, host_ring_mask(n));
-    return check_launch();
+    return launch(sign_mask_kernel, elementwise_grid(batch), 256, 0, static_cast<hipStream_t>(stream), alpha_share, d_y_share, d_masked,
+                  batch, host_ring_mask(n));
+}
+
+struct StreamEvents {
+    hipEvent_t copied[2];     // half h holds its chunk
+    hipEvent_t consumed[2];   // half h has been evaluated and may be overwritten
+};
+
+static int streamed_args_ok(int party, int n, size_t batch, size_t chunk, const void *h_key_chunks, const uint32_t *d_x,
+                            uint32_t *d_out, fss_stream_t copy_stream, fss_stream_t stream)
+{
+    if (bad_n(n) || (party != 0 && party != 1) || bad_count(batch) || bad_count(chunk) || chunk == 0 || chunk % 64 != 0) return FSS_EINVAL;
+    if (batch == 0) return FSS_OK;
+    if (!h_key_chunks || !d_x || !d_out || misaligned(d_x, 4) || misaligned(d_out, 4)) return FSS_EINVAL;
+    if (copy_stream == stream) return FSS_EINVAL;
+    return FSS_OK;
+}
+
+// Chunk c + 1 is copied host-to-device on the copy stream into one half of `staging` while chunk c
+// is evaluated out of the other half; returns after the last chunk has been evaluated (the halves
+// and the events must outlive the enqueued work).
+static int streamed_walk(int party, int n, size_t batch, size_t chunk, const void *h_key_chunks, const uint32_t *d_x,
+                         uint32_t *d_out, uint8_t *staging, const StreamEvents &ev, fss_stream_t copy_stream, fss_stream_t stream)
+{
+    hipStream_t cs = static_cast<hipStream_t>(copy_stream), es = static_cast<hipStream_t>(stream);
+    const size_t chunk_bytes = key_layout(true, n, chunk).total;
+    uint8_t *stage[2] = { staging, staging + chunk_bytes };
+    int rc = FSS_OK;
+    hipError_t err = hipSuccess;
+    const uint8_t *src = static_cast<const uint8_t *>(h_key_chunks);
+    const size_t nchunks = (batch + chunk - 1) / chunk;
+    for (size_t c = 0; c < nchunks && err == hipSuccess && rc == FSS_OK; c++) {
+        const int h = (int)(c & 1);
+        const size_t first = c * chunk, len = (batch - first < chunk) ? batch - first : chunk;
+        const size_t bytes = key_layout(true, n, len).total;
+        if (c >= 2) err = hipStreamWaitEvent(cs, ev.consumed[h], 0);          // the half is free again
+        if (err == hipSuccess) err = hipMemcpyAsync(stage[h], src, bytes, hipMemcpyHostToDevice, cs);
+        if (err == hipSuccess) err = hipEventRecord(ev.copied[h], cs);
+        if (err == hipSuccess) err = hipStreamWaitEvent(es, ev.copied[h], 0);
+        if (err != hipSuccess) break;
+        rc = eval_common(true, kPlain, party, n, len, stage[h], d_x + first, nullptr, d_out + first, nullptr, nullptr, nullptr,
+                         nullptr, stream);
+        if (rc == FSS_OK) err = hipEventRecord(ev.consumed[h], es);
+        src += bytes;
+    }
+    const hipError_t e2 = hipStreamSynchronize(cs);
+    const hipError_t e3 = hipStreamSynchronize(es);
+    if (err == hipSuccess) err = e2 != hipSuccess ? e2 : e3;
+    if (err != hipSuccess) { g_last_hip_error = (int)err; return FSS_ELAUNCH; }
+    return rc;
 }
 
 }  // namespace fss
@@ -864,9 +916,8 @@ int fss_argmax_diff_mask(int n, size_t rows, int m, const void *d_cmp_key, const
     if (rows == 0) return FSS_OK;
     if (!d_cmp_key || misaligned(d_cmp_key, 256) || bad_u32_ptr(d_x_share) || bad_u32_ptr(d_masked)) return FSS_EINVAL;
     const uint32_t *alpha_share = reinterpret_cast<const uint32_t *>(static_cast<const uint8_t *>(d_cmp_key) + key_layout(true, n, batch).alpha_share);
-    hipLaunchKernelGGL(argmax_diff_mask_kernel, dim3(elementwise_grid(batch)), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       alpha_share, d_x_share, d_masked, rows, (uint32_t)m, host_ring_mask(n));
-    return check_launch();
+    return launch(argmax_diff_mask_kernel, elementwise_grid(batch), 256, 0, static_cast<hipStream_t>(stream), alpha_share, d_x_share,
+                  d_masked, rows, (uint32_t)m, host_ring_mask(n));
 }
 
 int fss_argmax_count_mask(int party, int n, size_t rows, int m, const uint32_t *d_w_share, const void *d_eq_key,
@@ -879,9 +930,8 @@ int fss_argmax_count_mask(int party, int n, size_t rows, int m, const uint32_t *
     if (rows == 0) return FSS_OK;
     if (!d_eq_key || misaligned(d_eq_key, 256) || bad_u32_ptr(d_w_share) || bad_u32_ptr(d_masked)) return FSS_EINVAL;
     const uint32_t *alpha_share = reinterpret_cast<const uint32_t *>(static_cast<const uint8_t *>(d_eq_key) + key_layout(false, n, batch).alpha_share);
-    hipLaunchKernelGGL(argmax_count_mask_kernel, dim3(elementwise_grid(batch)), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       alpha_share, d_w_share, d_masked, batch, (uint32_t)m, host_ring_mask(n), party);
-    return check_launch();
+    return launch(argmax_count_mask_kernel, elementwise_grid(batch), 256, 0, static_cast<hipStream_t>(stream), alpha_share, d_w_share,
+                  d_masked, batch, (uint32_t)m, host_ring_mask(n), party);
 }
 
 int fss_maxpool_unroll(size_t channels, int h, int w, int k, int s, const uint32_t *d_x_share, uint32_t *d_rows, fss_stream_t stream)
@@ -893,9 +943,8 @@ int fss_maxpool_unroll(size_t channels, int h, int w, int k, int s, const uint32
     if (bad_count(total) || bad_count(checked_product(channels, checked_product((size_t)h, (size_t)w)))) return FSS_EINVAL;
     if (channels == 0) return FSS_OK;
     if (bad_u32_ptr(d_x_share) || bad_u32_ptr(d_rows)) return FSS_EINVAL;
-    hipLaunchKernelGGL(maxpool_unroll_kernel, dim3(elementwise_grid(total)), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       d_x_share, d_rows, channels, h, w, k, s, oh, ow);
-    return check_launch();
+    return launch(maxpool_unroll_kernel, elementwise_grid(total), 256, 0, static_cast<hipStream_t>(stream), d_x_share, d_rows, channels,
+                  h, w, k, s, oh, ow);
 }
 
 int fss_mul_open(int n, size_t count, const uint32_t *d_u_share, const uint32_t *d_v_share, const uint32_t *d_tri_a,
@@ -907,9 +956,8 @@ int fss_mul_open(int n, size_t count, const uint32_t *d_u_share, const uint32_t 
     if (bad_u32_ptr(d_u_share) || bad_u32_ptr(d_v_share) || bad_u32_ptr(d_tri_a) || bad_u32_ptr(d_tri_b) || bad_u32_ptr(d_delta) ||
         bad_u32_ptr(d_eps))
         return FSS_EINVAL;
-    hipLaunchKernelGGL(mul_open_kernel, dim3(elementwise_grid(count)), dim3(256), 0, static_cast<hipStream_t>(stream), d_u_share,
-                       d_v_share, d_tri_a, d_tri_b, d_delta, d_eps, count, host_ring_mask(n));
-    return check_launch();
+    return launch(mul_open_kernel, elementwise_grid(count), 256, 0, static_cast<hipStream_t>(stream), d_u_share, d_v_share, d_tri_a,
+                  d_tri_b, d_delta, d_eps, count, host_ring_mask(n));
 }
 
 int fss_dot_finish(int party, int n, size_t rows, int m, const uint32_t *d_delta0, const uint32_t *d_delta1, const uint32_t *d_eps0,
@@ -922,9 +970,8 @@ int fss_dot_finish(int party, int n, size_t rows, int m, const uint32_t *d_delta
     const void *ptrs[8] = { d_delta0, d_delta1, d_eps0, d_eps1, d_tri_a, d_tri_b, d_tri_c, d_out };
     for (int i = 0; i < 8; i++)
         if (bad_u32_ptr(ptrs[i])) return FSS_EINVAL;
-    hipLaunchKernelGGL(dot_finish_kernel, dim3(elementwise_grid(rows)), dim3(256), 0, static_cast<hipStream_t>(stream), d_delta0,
-                       d_delta1, d_eps0, d_eps1, d_tri_a, d_tri_b, d_tri_c, d_out, rows, (uint32_t)m, host_ring_mask(n), party);
-    return check_launch();
+    return launch(dot_finish_kernel, elementwise_grid(rows), 256, 0, static_cast<hipStream_t>(stream), d_delta0, d_delta1, d_eps0,
+                  d_eps1, d_tri_a, d_tri_b, d_tri_c, d_out, rows, (uint32_t)m, host_ring_mask(n), party);
 }
 
 int fss_sign_eval(int party, int n, size_t batch, const void *d_key, const uint32_t *d_masked0, const uint32_t *d_masked1,
@@ -952,9 +999,8 @@ int fss_relu_finish(int party, int n, size_t batch, const uint32_t *d_delta0, co
     for (int i = 0; i < 8; i++)
         if (bad_u32_ptr(ptrs[i])) return FSS_EINVAL;
     const uint32_t mask = host_ring_mask(n);
-    hipLaunchKernelGGL(relu_finish_kernel, dim3(elementwise_grid(batch)), dim3(256), 0, static_cast<hipStream_t>(stream), d_delta0,
-                       d_delta1, d_eps0, d_eps1, d_tri_a, d_tri_b, d_tri_c, d_out, batch, mask, party);
-    return check_launch();
+    return launch(relu_finish_kernel, elementwise_grid(batch), 256, 0, static_cast<hipStream_t>(stream), d_delta0, d_delta1, d_eps0,
+                  d_eps1, d_tri_a, d_tri_b, d_tri_c, d_out, batch, mask, party);
 }
 
 size_t fss_cmp_chunked_key_bytes(int n, size_t batch, size_t chunk)
@@ -968,47 +1014,29 @@ int fss_cmp_eval_streamed(int party, int n, size_t batch, size_t chunk, const vo
                           uint32_t *d_out, void *d_staging, fss_stream_t copy_stream, fss_stream_t stream)
 {
     using namespace fss;
-    if (bad_n(n) || (party != 0 && party != 1) || bad_count(batch) || bad_count(chunk) || chunk == 0 || chunk % 64 != 0) return FSS_EINVAL;
-    if (batch == 0) return FSS_OK;
-    if (!h_key_chunks || !d_x || !d_out || !d_staging || misaligned(d_staging, 256) || misaligned(d_x, 4) || misaligned(d_out, 4))
-        return FSS_EINVAL;
-    if (copy_stream == stream) return FSS_EINVAL;
-    hipStream_t cs = static_cast<hipStream_t>(copy_stream), es = static_cast<hipStream_t>(stream);
-    const size_t chunk_bytes = key_layout(true, n, chunk).total;
-    uint8_t *stage[2] = { static_cast<uint8_t *>(d_staging), static_cast<uint8_t *>(d_staging) + chunk_bytes };
-    hipEvent_t copied[2] = { nullptr, nullptr }, consumed[2] = { nullptr, nullptr };
-    int rc = FSS_OK;
+    const int rc = streamed_args_ok(party, n, batch, chunk, h_key_chunks, d_x, d_out, copy_stream, stream);
+    if (rc != FSS_OK || batch == 0) return rc;
+    if (!d_staging || misaligned(d_staging, 256)) return FSS_EINVAL;
+    StreamEvents ev = {};
     hipError_t err = hipSuccess;
     for (int i = 0; i < 2 && err == hipSuccess; i++) {
-        err = hipEventCreateWithFlags(&copied[i], hipEventDisableTiming);
-        if (err == hipSuccess) err = hipEventCreateWithFlags(&consumed[i], hipEventDisableTiming);
+        err = hipEventCreateWithFlags(&ev.copied[i], hipEventDisableTiming);
+        if (err == hipSuccess) err = hipEventCreateWithFlags(&ev.consumed[i], hipEventDisableTiming);
     }
-    const uint8_t *src = static_cast<const uint8_t *>(h_key_chunks);
-    const size_t nchunks = (batch + chunk - 1) / chunk;
-    for (size_t c = 0; c < nchunks && err == hipSuccess && rc == FSS_OK; c++) {
-        const int h = (int)(c & 1);
-        const size_t first = c * chunk, len = (batch - first < chunk) ? batch - first : chunk;
-        const size_t bytes = key_layout(true, n, len).total;
-        if (c >= 2) err = hipStreamWaitEvent(cs, consumed[h], 0);          // the half is free again
-        if (err == hipSuccess) err = hipMemcpyAsync(stage[h], src, bytes, hipMemcpyHostToDevice, cs);
-        if (err == hipSuccess) err = hipEventRecord(copied[h], cs);
-        if (err == hipSuccess) err = hipStreamWaitEvent(es, copied[h], 0);
-        if (err != hipSuccess) break;
-        rc = eval_common(true, kPlain, party, n, len, stage[h], d_x + first, nullptr, d_out + first, nullptr, nullptr, nullptr,
-                         nullptr, stream);
-        if (rc == FSS_OK) err = hipEventRecord(consumed[h], es);
-        src += bytes;
-    }
-    // the staging halves and the events must outlive the enqueued work
-    hipError_t e2 = hipStreamSynchronize(cs);
-    hipError_t e3 = hipStreamSynchronize(es);
+    int out = FSS_OK;
+    if (err != hipSuccess) { g_last_hip_error = (int)err; out = FSS_ELAUNCH; }
+    else out = streamed_walk(party, n, batch, chunk, h_key_chunks, d_x, d_out, static_cast<uint8_t *>(d_staging), ev, copy_stream, stream);
     for (int i = 0; i < 2; i++) {
-        if (copied[i]) (void)hipEventDestroy(copied[i]);
-        if (consumed[i]) (void)hipEventDestroy(consumed[i]);
+        if (ev.copied[i]) (void)hipEventDestroy(ev.copied[i]);
+        if (ev.consumed[i]) (void)hipEventDestroy(ev.consumed[i]);
     }
-    if (err == hipSuccess) err = e2 != hipSuccess ? e2 : e3;
-    if (err != hipSuccess) { g_last_hip_error = (int)err; return FSS_ELAUNCH; }
-    return rc;
+    return out;
+}
+
+int fss_prepare(void)
+{
+    fss::DeviceInfo dev;
+    return fss::prepare_device(&dev);
 }
 
 size_t fss_quad_layout_below(void)
@@ -1024,6 +1052,7 @@ const char *fss_strerror(int code)
     case FSS_EINVAL: return "invalid argument (party, n, element count above 2^40, NULL/misaligned/overlapping pointer)";
     case FSS_ELAUNCH: return "HIP runtime error while preparing or launching a kernel";
     case FSS_EDEVICE: return "device unsupported: kernels need 128 KiB of LDS per workgroup";
+    case FSS_ELIMIT: return "size beyond the fixed limit of this entry point (chunk too large for the built-in staging memory)";
     default: return "unknown fss error code";
     }
 }

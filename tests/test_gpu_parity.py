@@ -221,6 +221,8 @@ def test_values_above_the_ring_are_reduced():
 
 
 def test_empty_batch_is_a_noop_and_errors_raise():
+    fss.prepare()                                   # idempotent per-device set-up
+    fss.prepare()
     fss.cmp_eval(0, 32, 0, None, None, None)
     fss.eq_gen(32, 0, None, None, None, None, None, None)
     with pytest.raises(fss.FssError):
