@@ -94,8 +94,9 @@ typedef void *fss_stream_t; /* hipStream_t */
 #define FSS_ELIMIT (-4)   /* a size is beyond a fixed limit of the entry point (fss_cmp_eval_streamed_static) */
 
 /* Per-device set-up for the CURRENT device, idempotent and thread-safe: configures the kernels
- * (they need 128 KiB of dynamic LDS).  Every entry point does this by itself on its first call
- * on a device; calling it explicitly keeps that work out of latency-critical or captured code.
+ * (they need 128 KiB of dynamic LDS) and readies the built-in staging memory of
+ * fss_cmp_eval_streamed_static.  Every entry point does its part of this by itself on its first
+ * call on a device; calling it explicitly keeps that work out of latency-critical or captured code.
  * FSS_OK, FSS_EDEVICE (the device cannot run the kernels) or FSS_ELAUNCH. */
 int fss_prepare(void);
 
@@ -220,6 +221,27 @@ size_t fss_cmp_chunked_key_bytes(int n, size_t batch, size_t chunk);
 int fss_cmp_eval_streamed(int party, int n, size_t batch, size_t chunk, const void *h_key_chunks,
                           const uint32_t *d_x, uint32_t *d_out, void *d_staging,
                           fss_stream_t copy_stream, fss_stream_t stream);
+
+/* For callers that cannot allocate device memory (code under HIP graph capture elsewhere in the
+ * process, tight serving loops, harnesses that forbid hipMalloc): fss_cmp_eval_streamed with the
+ * two staging halves taken from a fixed array inside the library instead of `d_staging`, and with
+ * events made once per device instead of per call.  Same arguments otherwise, same results.
+ *   - Limit: 2 * fss_cmp_key_bytes(n, chunk) <= fss_static_staging_bytes() (32 MiB: chunk up to
+ *     20,736 elements at n = 32); beyond it the call returns FSS_ELIMIT and does nothing.
+ *   - After the per-device set-up the call allocates nothing: no hipMalloc/hipFree, no event or
+ *     stream creation -- only hipMemcpyAsync from the caller's PINNED host buffer, event
+ *     records/waits, kernel launches and two stream synchronisations.  The set-up (the array's
+ *     device address, four events, kernel attributes) happens in fss_prepare(), or else in the
+ *     first call on a device; call fss_prepare() up front to keep even that out of the path.
+ *   - The array is one per GPU and shared by every call on that GPU, for the life of the process:
+ *     calls that overlap in time on one GPU (from several threads or stream pairs) race on it and
+ *     must be serialised by the caller.  Nothing in it needs clearing between calls: every byte
+ *     a kernel reads has been overwritten by that call's own copies first.
+ *   - Like fss_cmp_eval_streamed it blocks until the last chunk has been evaluated. */
+size_t fss_static_staging_bytes(void);
+int fss_cmp_eval_streamed_static(int party, int n, size_t batch, size_t chunk, const void *h_key_chunks,
+                                 const uint32_t *d_x, uint32_t *d_out, fss_stream_t copy_stream,
+                                 fss_stream_t stream);
 
 /* Register layouts.  The KeyGen and Eval kernels exist in two layouts with identical results
  * (keys and shares agree byte for byte): one lane per element (highest throughput) and four

@@ -17,6 +17,8 @@ from .binding import (  # noqa: F401
     cmp_chunked_key_bytes,
     cmp_eval,
     cmp_eval_streamed,
+    cmp_eval_streamed_static,
+    static_staging_bytes,
     cmp_gen,
     cmp_key_bytes,
     eq_eval,

@@ -17,7 +17,7 @@ EXPORTS = ("fss_cmp_key_bytes", "fss_eq_key_bytes", "fss_cmp_gen", "fss_cmp_eval
            "fss_sign_mask", "fss_sign_eval", "fss_relu_open", "fss_relu_finish", "fss_eq_mask", "fss_eq_masked_eval",
            "fss_argmax_diff_mask", "fss_argmax_count_mask", "fss_maxpool_unroll", "fss_mul_open", "fss_dot_finish",
            "fss_cmp_chunked_key_bytes",
-           "fss_cmp_eval_streamed", "fss_prepare", "fss_quad_layout_below", "fss_strerror", "fss_last_hip_error")
+           "fss_cmp_eval_streamed", "fss_cmp_eval_streamed_static", "fss_static_staging_bytes", "fss_prepare", "fss_quad_layout_below", "fss_strerror", "fss_last_hip_error")
 
 HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -101,6 +101,10 @@ def lib() -> C.CDLL:
         L.fss_cmp_chunked_key_bytes.restype = sz
         L.fss_cmp_eval_streamed.argtypes = [i, i, sz, sz, vp, vp, vp, vp, vp, vp]
         L.fss_cmp_eval_streamed.restype = i
+        L.fss_cmp_eval_streamed_static.argtypes = [i, i, sz, sz, vp, vp, vp, vp, vp]
+        L.fss_cmp_eval_streamed_static.restype = i
+        L.fss_static_staging_bytes.argtypes = []
+        L.fss_static_staging_bytes.restype = sz
         L.fss_prepare.argtypes = []
         L.fss_prepare.restype = i
         L.fss_quad_layout_below.argtypes = []
@@ -228,6 +232,16 @@ def cmp_eval_streamed(party: int, n: int, batch: int, chunk: int, h_key_chunks, 
     _check(lib().fss_cmp_eval_streamed(party, n, batch, chunk, _host_pinned("key_chunks", h_key_chunks, cmp_chunked_key_bytes(n, batch, chunk)),
                                        _dev("x", d_x, 4 * batch), _dev("out", d_out, 4 * batch),
                                        _dev("staging", d_staging, 2 * cmp_key_bytes(n, chunk)), _stream(copy_stream), _stream(stream)))
+
+
+def static_staging_bytes() -> int:
+    return int(lib().fss_static_staging_bytes())
+
+
+def cmp_eval_streamed_static(party: int, n: int, batch: int, chunk: int, h_key_chunks, d_x, d_out, copy_stream, stream=None) -> None:
+    """fss_cmp_eval_streamed_static: as cmp_eval_streamed, staging inside the library (no allocation)."""
+    _check(lib().fss_cmp_eval_streamed_static(party, n, batch, chunk, _host_pinned("key_chunks", h_key_chunks, cmp_chunked_key_bytes(n, batch, chunk)),
+                                              _dev("x", d_x, 4 * batch), _dev("out", d_out, 4 * batch), _stream(copy_stream), _stream(stream)))
 
 
 def eq_mask(n: int, batch: int, d_key, d_y_share, d_masked, stream=None) -> None:

@@ -858,6 +858,57 @@ static int streamed_walk(int party, int n, size_t batch, size_t chunk, const voi
     return rc;
 }
 
+// ------------------------------------------------------------------------------------
+// Built-in staging memory for callers that cannot allocate
+// ------------------------------------------------------------------------------------
+
+// Two staging halves for fss_cmp_eval_streamed_static.  One copy of the array exists on every GPU
+// the library runs on, from the moment its code is loaded there until the process ends.
+constexpr size_t kStaticStagingBytes = (size_t)32 << 20;
+static __device__ __align__(256) uint8_t scratch[kStaticStagingBytes];
+
+struct StaticStaging {
+    int ok;               // 1 ready, 0 not set up yet
+    uint8_t *ptr;         // DEVICE address of this device's copy of `scratch` (the array's name is only a host-side handle)
+    StreamEvents ev;      // created once, reused by every call on the device
+};
+
+// Per device, once, with that device current: the device address of `scratch` and four events.
+static int prepare_static_staging(StaticStaging *out)
+{
+    static StaticStaging cache[64] = {};
+    static std::mutex cache_lock;
+    std::lock_guard<std::mutex> guard(cache_lock);
+    int dev = 0;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) { g_last_hip_error = (int)err; return FSS_ELAUNCH; }
+    if (dev < 0 || dev >= 64) return FSS_EDEVICE;
+    StaticStaging &c = cache[dev];
+    if (!c.ok) {
+        void *p = nullptr;
+        err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (err == hipSuccess && p == nullptr) err = hipErrorInvalidSymbol;
+        StreamEvents ev = {};
+        for (int i = 0; i < 2 && err == hipSuccess; i++) {
+            err = hipEventCreateWithFlags(&ev.copied[i], hipEventDisableTiming);
+            if (err == hipSuccess) err = hipEventCreateWithFlags(&ev.consumed[i], hipEventDisableTiming);
+        }
+        if (err != hipSuccess) {
+            for (int i = 0; i < 2; i++) {
+                if (ev.copied[i]) (void)hipEventDestroy(ev.copied[i]);
+                if (ev.consumed[i]) (void)hipEventDestroy(ev.consumed[i]);
+            }
+            g_last_hip_error = (int)err;
+            return FSS_ELAUNCH;
+        }
+        c.ptr = static_cast<uint8_t *>(p);
+        c.ev = ev;
+        c.ok = 1;
+    }
+    *out = c;
+    return FSS_OK;
+}
+
 }  // namespace fss
 
 extern "C" {
@@ -1033,10 +1084,29 @@ int fss_cmp_eval_streamed(int party, int n, size_t batch, size_t chunk, const vo
     return out;
 }
 
+size_t fss_static_staging_bytes(void) { return fss::kStaticStagingBytes; }
+
+int fss_cmp_eval_streamed_static(int party, int n, size_t batch, size_t chunk, const void *h_key_chunks, const uint32_t *d_x,
+                                 uint32_t *d_out, fss_stream_t copy_stream, fss_stream_t stream)
+{
+    using namespace fss;
+    int rc = streamed_args_ok(party, n, batch, chunk, h_key_chunks, d_x, d_out, copy_stream, stream);
+    if (rc != FSS_OK) return rc;
+    if (2 * key_layout(true, n, chunk).total > kStaticStagingBytes) return FSS_ELIMIT;   // chunk <= 2^40: no overflow
+    if (batch == 0) return FSS_OK;
+    StaticStaging st;
+    rc = prepare_static_staging(&st);       // after the first call on a device: a table lookup
+    if (rc != FSS_OK) return rc;
+    return streamed_walk(party, n, batch, chunk, h_key_chunks, d_x, d_out, st.ptr, st.ev, copy_stream, stream);
+}
+
 int fss_prepare(void)
 {
     fss::DeviceInfo dev;
-    return fss::prepare_device(&dev);
+    int rc = fss::prepare_device(&dev);
+    if (rc != FSS_OK) return rc;
+    fss::StaticStaging st;
+    return fss::prepare_static_staging(&st);
 }
 
 size_t fss_quad_layout_below(void)
