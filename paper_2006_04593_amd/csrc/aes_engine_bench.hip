@@ -2,8 +2,9 @@
 //   1. raw Matyas-Meyer-Oseas blocks/s of the LDS-table engine (aes_lds.h), as the kernels use it;
 //   2. the same for the ALU-only bit-plane engine (aes_bitplane.h);
 //   3. the machine rates that bound them: conflict-free ds_read_b32 lookups per clock per CU
-//      (the kernel's 32-copy access pattern and an unreplicated table for comparison), and the
-//      issue rate of the vector-ALU instructions both engines are made of;
+//      (the kernel's 32-copy access pattern and an unreplicated table for comparison), the LDS
+//      read port by access width (b32 / b64 / b128), and the issue rate of the vector-ALU
+//      instructions both engines are made of;
 //   4. the LDS-table engine in its four-lanes-per-block layout (aes_quad.h);
 //   5. whether the vector-memory path could carry some of the lookups beside the LDS (gathers
 //      from a 1-KiB table that stays in the L1 cache);
@@ -175,6 +176,59 @@ __global__ __launch_bounds__(kThreads) void lds_rate(uint32_t *out, int iters)
     out[blockIdx.x * blockDim.x + threadIdx.x] = acc;
 }
 
+// ---- machine rate of the LDS read port by access width: ds_read_b32 / _b64 / _b128 with
+// data-dependent per-lane addresses that are conflict-free by construction.  Every entry owns 256
+// bytes (the kernels' stride); a lane reads WIDTH bytes at offset (lane mod COPIES) * WIDTH inside
+// a pseudo-random entry, so any COPIES consecutive lanes cover COPIES * WIDTH distinct consecutive
+// bytes' worth of banks whatever the entries are:
+//   WIDTH 4, COPIES 32: the kernels' pattern (lanes l and l + 32 share a bank);
+//   WIDTH 4, COPIES 64: one bank per lane if the LDS had 64 independent banks for 32-bit reads;
+//   WIDTH 8, COPIES 32 and WIDTH 16, COPIES 16: 256 bytes per 32 (16) lanes.
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <int WIDTH, int COPIES>
+__global__ __launch_bounds__(kThreads) void lds_width_rate(uint32_t *out, int iters)
+{
+    static_assert(WIDTH * COPIES <= 256, "a lane's read stays inside its entry");
+    extern __shared__ uint32_t lds[];
+    for (uint32_t j = threadIdx.x; j < kLdsBytes / 4; j += blockDim.x) lds[j] = j * 2654435761u;
+    __syncthreads();
+    const uint32_t off = (threadIdx.x % COPIES) * WIDTH;
+    uint32_t r = threadIdx.x * 747796405u + blockIdx.x * 2891336453u + 12345u, acc = 0;
+    uint32_t a[8];
+#pragma unroll
+    for (int k = 0; k < 8; k++) {
+        r = r * 1664525u + 1013904223u;
+        a[k] = (((r >> 13) & 511u) << 8) | off;         // 512 entries x 256 B = the 128 KiB that were filled
+    }
+    for (int it = 0; it < iters; it++) {
+        if constexpr (WIDTH == 4) {
+            uint32_t v[8];
+#pragma unroll
+            for (int k = 0; k < 8; k++) asm volatile("ds_read_b32 %0, %1" : "=v"(v[k]) : "v"(a[k]) : "memory");
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]), "+v"(v[6]), "+v"(v[7]) : : "memory");
+#pragma unroll
+            for (int k = 0; k < 8; k++) acc ^= v[k];
+        } else if constexpr (WIDTH == 8) {
+            u32x2 v[8];
+#pragma unroll
+            for (int k = 0; k < 8; k++) asm volatile("ds_read_b64 %0, %1" : "=v"(v[k]) : "v"(a[k]) : "memory");
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]), "+v"(v[6]), "+v"(v[7]) : : "memory");
+#pragma unroll
+            for (int k = 0; k < 8; k++) acc ^= v[k].x ^ v[k].y;
+        } else {
+            u32x4 v[8];
+#pragma unroll
+            for (int k = 0; k < 8; k++) asm volatile("ds_read_b128 %0, %1" : "=v"(v[k]) : "v"(a[k]) : "memory");
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]), "+v"(v[6]), "+v"(v[7]) : : "memory");
+#pragma unroll
+            for (int k = 0; k < 8; k++) acc ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
+        }
+    }
+    out[blockIdx.x * blockDim.x + threadIdx.x] = acc;
+}
+
 // ---- machine rate: vector-ALU instructions, 8 independent chains per wavefront
 #define FSS_ALU_LOOP(INSTRS)                                                                                  \
     asm volatile("v_mov_b32 v10, %1\n v_mov_b32 v11, %1\n v_mov_b32 v12, %1\n v_mov_b32 v13, %1\n"            \
@@ -267,6 +321,29 @@ int main()
         if (time_launch([&] { hipLaunchKernelGGL(lds_rate<false>, dim3(cus), dim3(kThreads), kLdsBytes, 0, out, iters); }, &ms)) return 1;
         printf("  one 1-KiB table, no replication       %8.3f ms  %6.1f lookups/clk/CU  %6.1f TB/s\n", ms,
                lanes / (ms * 1e-3) / cus / (ghz * 1e9), lanes * 4 / (ms * 1e-3) / 1e12);
+    }
+
+    printf("\nLDS read port by access width: conflict-free per-lane addresses (random 256-byte entry, own slot inside it), 16 wavefronts per CU\n");
+    {
+        const int iters = 20000;
+        const double reads = (double)cus * kThreads * iters * 8;
+        struct { const char *name; int width; const void *fn; } rows[4] = {
+            { "ds_read_b32,  32 slots of 4 B  (kernels' pattern)", 4, (const void *)lds_width_rate<4, 32> },
+            { "ds_read_b32,  64 slots of 4 B  (one bank per lane)", 4, (const void *)lds_width_rate<4, 64> },
+            { "ds_read_b64,  32 slots of 8 B", 8, (const void *)lds_width_rate<8, 32> },
+            { "ds_read_b128, 16 slots of 16 B", 16, (const void *)lds_width_rate<16, 16> },
+        };
+        for (int i = 0; i < 4; i++) {
+            CK(hipFuncSetAttribute(rows[i].fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes));
+            uint32_t *o = out;
+            int it = iters;
+            void *args[2] = { &o, &it };
+            const void *fn = rows[i].fn;
+            if (time_launch([&] { (void)hipLaunchKernel(fn, dim3(cus), dim3(kThreads), args, kLdsBytes, 0); }, &ms)) return 1;
+            printf("  %-52s %8.3f ms  %6.1f reads/clk/CU  %6.1f B/clk/CU  %6.1f TB/s\n", rows[i].name, ms,
+                   reads / (ms * 1e-3) / cus / (ghz * 1e9), reads * rows[i].width / (ms * 1e-3) / cus / (ghz * 1e9),
+                   reads * rows[i].width / (ms * 1e-3) / 1e12);
+        }
     }
 
     printf("\nvector-ALU issue rate, 4 wavefronts per SIMD, 8 independent chains\n");

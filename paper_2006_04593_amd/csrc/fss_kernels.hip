@@ -23,6 +23,32 @@ namespace fss {
 
 __device__ __forceinline__ uint32_t ring_mask(int n) { return n == 32 ? 0xffffffffu : ((1u << n) - 1u); }
 
+// Wavefront priority by progress through the tile.  A SIMD issues from its OLDEST wavefront first,
+// so with equal priorities the first wavefront of every SIMD runs at full speed and the youngest
+// is starved: they drift a whole tile apart per pass, the old ones finish all their tiles early,
+// and the launch ends with a long stretch in which too few wavefronts are left to keep the LDS
+// busy (measured: the four wavefronts of a SIMD finish 30 us apart after ONE 64-element tile).
+// Lowering a wavefront's priority as it advances (3 in the first half of the walk, then 2, 1, 0
+// from n/2, 3n/4 and 7n/8 on) lets the ones behind catch up, so that they finish together.
+// Cost: one scalar compare per level (`i == next`), three priority changes per tile.  `balance` is
+// false for launches with at most one working wavefront per SIMD, where there is nobody to wait for
+// (the level loop of such a launch is pure latency, and even untaken branches count there).
+__device__ __forceinline__ int tile_priority_start(int n, bool balance)
+{
+    if (!balance) return -1;
+    __builtin_amdgcn_s_setprio(3);
+    return n >> 1;
+}
+
+// called when level i has reached the threshold `next`; returns the next threshold
+__device__ __forceinline__ int lower_priority(int i, int n)
+{
+    if (i < n - (n >> 2)) { __builtin_amdgcn_s_setprio(2); return n - (n >> 2); }
+    if (i < n - (n >> 3)) { __builtin_amdgcn_s_setprio(1); return n - (n >> 3); }
+    __builtin_amdgcn_s_setprio(0);
+    return -1;
+}
+
 // What the evaluation kernel reads as its public input and writes as its result.
 //   kPlain:    x given; out = share of f(x)                                   (Algorithms 2, 4)
 //   kSign:     x = x[e] + x2[e] (the two published masked shares)              (Algorithm 5)
@@ -43,6 +69,7 @@ struct EvalArgs {
     size_t batch;
     int n;
     int party;
+    int balance;               // more than one working wavefront per SIMD: equalise their progress (progress priority)
 };
 
 struct GenArgs {
@@ -54,6 +81,7 @@ struct GenArgs {
     uint8_t *key1;
     size_t batch;
     int n;
+    int balance;               // as in EvalArgs
 };
 
 // ------------------------------------------------------------------------------------
@@ -104,7 +132,9 @@ __global__ __launch_bounds__(kThreads) void eval_kernel(EvalArgs a)
         uint4 scw_next = scw_p[e];
         uint32_t sig_next = 0, leaf_next = 0;
         if constexpr (CMP) { sig_next = sig_p[e]; leaf_next = leaf_p[e]; }
+        int next_drop = tile_priority_start(n, a.balance != 0);
         for (int i = 0; i < n; i++) {                   // level i + 1
+            if (i == next_drop) next_drop = lower_priority(i, n);
             const uint4 scw = scw_next;
             const uint32_t sigcw = sig_next, leaf = leaf_next;
             if (i + 1 < n) {
@@ -203,7 +233,9 @@ __global__ __launch_bounds__(kThreads) void eval_quad_kernel(EvalArgs a)
         uint32_t scw_next = scw_p[4 * e + col];
         uint32_t sig_next = 0, leaf_next = 0;
         if constexpr (CMP) { sig_next = sig_p[e]; leaf_next = leaf_p[e]; }
+        int next_drop = tile_priority_start(n, a.balance != 0);
         for (int i = 0; i < n; i++) {
+            if (i == next_drop) next_drop = lower_priority(i, n);
             const uint32_t scw = scw_next, sigcw = sig_next, leaf = leaf_next;
             if (i + 1 < n) {
                 const size_t pe = (size_t)(i + 1) * k.bp + e;
@@ -405,7 +437,9 @@ __global__ __launch_bounds__(kThreads) void gen_kernel(GenArgs a)
         reinterpret_cast<uint4 *>(a.key0 + k.seed)[e] = make_uint4(s[0][0], s[0][1], s[0][2], s[0][3]);
         reinterpret_cast<uint4 *>(a.key1 + k.seed)[e] = make_uint4(s[1][0], s[1][1], s[1][2], s[1][3]);
 
+        int next_drop = tile_priority_start(n, a.balance != 0);
         for (int i = 0; i < n; i++) {                     // level i + 1
+            if (i == next_drop) next_drop = lower_priority(i, n);
             const uint32_t abit = (alpha >> (n - 1 - i)) & 1u;   // alpha[i]; Keep = abit, Lose = 1 - abit
             uint32_t g[2][3][4];                          // [party][G_1, G_2, G_3][word]
             if constexpr (CMP) {
@@ -535,7 +569,9 @@ __global__ __launch_bounds__(kThreads) void gen_quad_kernel(GenArgs a)
         reinterpret_cast<uint32_t *>(a.key0 + k.seed)[4 * e + col] = s[0];
         reinterpret_cast<uint32_t *>(a.key1 + k.seed)[4 * e + col] = s[1];
 
+        int next_drop = tile_priority_start(n, a.balance != 0);
         for (int i = 0; i < n; i++) {
+            if (i == next_drop) next_drop = lower_priority(i, n);
             const uint32_t abit = (alpha >> (n - 1 - i)) & 1u;
             uint32_t g[2][3];                             // [party][G_1, G_2, G_3], this lane's column
             if constexpr (CMP) {
@@ -680,6 +716,7 @@ static size_t checked_product(size_t a, size_t b)
 
 struct LaunchShape {
     unsigned grid, threads;
+    int balance;      // some SIMD gets more than one working wavefront
 };
 
 // One workgroup per CU (its tables take 128 KiB of the CU's LDS), always of 16 wavefronts: the
@@ -693,6 +730,7 @@ static LaunchShape shape_for(size_t elems, const DeviceInfo &d, size_t tile_elem
     LaunchShape s;
     s.threads = (unsigned)kThreads;
     s.grid = (unsigned)(tiles < cus ? tiles : cus);
+    s.balance = tiles > 4 * (size_t)s.grid;     // wavefront w of a workgroup runs on SIMD w mod 4
     return s;
 }
 
@@ -744,9 +782,11 @@ static int gen_common(bool cmp, int n, size_t batch, const uint32_t *d_alpha, co
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (use_quad_layout(batch, dev)) {
         const LaunchShape ls = shape_for(padded_batch(batch), dev, 16);
+        a.balance = ls.balance;
         return launch(cmp ? gen_quad_kernel<true> : gen_quad_kernel<false>, ls.grid, ls.threads, kLdsBytes, st, a);
     }
     const LaunchShape ls = shape_for(padded_batch(batch), dev);
+    a.balance = ls.balance;
     return launch(cmp ? gen_kernel<true> : gen_kernel<false>, ls.grid, ls.threads, kLdsBytes, st, a);
 }
 
@@ -772,6 +812,7 @@ static int eval_common(bool cmp, int mode, int party, int n, size_t batch, const
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool quad = use_quad_layout(batch, dev);
     const LaunchShape ls = shape_for(batch, dev, quad ? 16 : 64);
+    a.balance = ls.balance;
     void (*kernel)(EvalArgs);
     if (quad) {
         kernel = !cmp ? (mode == kPlain ? eval_quad_kernel<false, kPlain> : eval_quad_kernel<false, kSign>)
