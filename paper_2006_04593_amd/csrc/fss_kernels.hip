@@ -23,6 +23,9 @@ namespace fss {
 
 __device__ __forceinline__ uint32_t ring_mask(int n) { return n == 32 ? 0xffffffffu : ((1u << n) - 1u); }
 
+// index of the wavefront inside its workgroup, as a scalar: tile counters derived from it stay in scalar registers
+__device__ __forceinline__ uint32_t wave_index() { return __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); }
+
 // Wavefront priority by progress through the tile.  A SIMD issues from its OLDEST wavefront first,
 // so with equal priorities the first wavefront of every SIMD runs at full speed and the youngest
 // is starved: they drift a whole tile apart per pass, the old ones finish all their tiles early,
@@ -69,7 +72,8 @@ struct EvalArgs {
     size_t batch;
     int n;
     int party;
-    int balance;               // more than one working wavefront per SIMD: equalise their progress (progress priority)
+    size_t lane_tiles;         // eval_kernel: 64-element tiles walked one lane per element, from element 0
+    size_t quad_tiles;         // eval_kernel: 16-element tiles walked four lanes per element, after those
 };
 
 struct GenArgs {
@@ -81,116 +85,263 @@ struct GenArgs {
     uint8_t *key1;
     size_t batch;
     int n;
-    int balance;               // as in EvalArgs
+    size_t lane_tiles;         // gen_kernel: as in EvalArgs; quad_tiles reaches to the end of the padded batch
+    size_t quad_tiles;
 };
 
 // ------------------------------------------------------------------------------------
 // Eval: Algorithm 2 (CMP = false) and Algorithm 4 (CMP = true)
 // ------------------------------------------------------------------------------------
 
+struct EvalPlanes {
+    const uint4 *seed;
+    const uint8_t *ctrl;
+    const uint4 *scw;
+    const uint32_t *sig, *leaf, *last;
+    size_t bp;
+};
+
+__device__ __forceinline__ EvalPlanes eval_planes(const EvalArgs &a, const KeyLayout &k)
+{
+    EvalPlanes p;
+    p.seed = reinterpret_cast<const uint4 *>(a.key + k.seed);
+    p.ctrl = a.key + k.ctrl;
+    p.scw = reinterpret_cast<const uint4 *>(a.key + k.s_cw);
+    p.sig = reinterpret_cast<const uint32_t *>(a.key + k.sigma_cw);
+    p.leaf = reinterpret_cast<const uint32_t *>(a.key + k.leaf);
+    p.last = reinterpret_cast<const uint32_t *>(a.key + k.last);
+    p.bp = k.bp;
+    return p;
+}
+
+// What one lane reads before the first level of its element (one lane per element): requested a whole
+// tile ahead, so that it is in registers when the walk starts.
+template <bool CMP>
+struct LaneInputs {
+    uint4 seed;
+    uint4 ctrl;                 // t_CW^L, t_CW^R, tau_CW^L, tau_CW^R (equality: the first two)
+    uint32_t x;
+    uint4 scw;                  // correction words of level 1
+    uint32_t sig, leaf;
+};
+
+template <bool CMP, int MODE>
+__device__ __forceinline__ LaneInputs<CMP> load_lane_inputs(const EvalArgs &a, const EvalPlanes &p, size_t e)
+{
+    LaneInputs<CMP> in;
+    in.seed = p.seed[e];
+    if constexpr (CMP) {
+        in.ctrl = reinterpret_cast<const uint4 *>(p.ctrl)[e];
+    } else {
+        const uint2 c = reinterpret_cast<const uint2 *>(p.ctrl)[e];
+        in.ctrl = make_uint4(c.x, c.y, 0u, 0u);
+    }
+    uint32_t xin = a.x[e];
+    if constexpr (MODE != kPlain) xin += a.x2[e];        // the reveal: x = alpha + y
+    in.x = xin;
+    in.scw = p.scw[e];
+    in.sig = 0; in.leaf = 0;
+    if constexpr (CMP) { in.sig = p.sig[e]; in.leaf = p.leaf[e]; }
+    return in;
+}
+
+template <int MODE>
+__device__ __forceinline__ void store_share(const EvalArgs &a, size_t e, uint32_t acc, uint32_t mask)
+{
+    if (a.party) acc = 0u - acc;
+    acc &= mask;
+    if constexpr (MODE == kReluOpen) {
+        const uint32_t v = ((a.party ? 0u : 1u) - acc) & mask;     // share of 1{y > 0}
+        a.out[e] = (a.y_share[e] - a.tri_a[e]) & mask;
+        a.out2[e] = (v - a.tri_b[e]) & mask;
+    } else {
+        a.out[e] = acc;
+    }
+}
+
+// The walk of one element by one lane.
+template <bool CMP, int MODE>
+__device__ __forceinline__ void eval_lane_walk(const EvalArgs &a, const EvalPlanes &p, const LaneBase L, size_t e,
+                                               const LaneInputs<CMP> &in)
+{
+    const int n = a.n;
+    const uint32_t mask = ring_mask(n);
+    uint32_t s[4] = { in.seed.x & ~1u, in.seed.y, in.seed.z, in.seed.w };
+    uint32_t t = (uint32_t)a.party;                 // t^(1) = j
+    const uint32_t tcw[2] = { in.ctrl.x, in.ctrl.y }, taucw[2] = { in.ctrl.z, in.ctrl.w };
+    const uint32_t x = in.x & mask;
+    uint32_t acc = 0;
+
+    // correction words are fetched one level ahead of their use
+    uint4 scw_next = in.scw;
+    uint32_t sig_next = in.sig, leaf_next = in.leaf;
+    int next_drop = tile_priority_start(n, true);
+    for (int i = 0; i < n; i++) {                   // level i + 1
+        if (i == next_drop) next_drop = lower_priority(i, n);
+        const uint4 scw = scw_next;
+        const uint32_t sigcw = sig_next, leaf = leaf_next;
+        if (i + 1 < n) {
+            const size_t pe = (size_t)(i + 1) * p.bp + e;
+            scw_next = p.scw[pe];
+            if constexpr (CMP) { sig_next = p.sig[pe]; leaf_next = p.leaf[pe]; }
+        }
+        const uint32_t b = (x >> (n - 1 - i)) & 1u;  // x[i], most significant first
+        const bool right = b != 0;
+        const uint32_t pick = 0u - b;                // all ones iff x[i] = 1
+        const uint32_t tm = 0u - t;                  // all ones iff t = 1
+
+        uint32_t child[4];
+        if constexpr (CMP) {
+            uint32_t g[2][4];
+            const uint32_t pk[2] = { pick, 0u };
+            aes_mmo_same_input<kNeedSigmaTau, -1, 2>(g, s, pk, L);  // G_{1+x[i]}(s) and G_3(s)
+            const uint32_t sigma = ((right ? g[1][1] : g[1][0]) ^ (sigcw & tm)) & mask;
+            const uint32_t tau = ((g[1][2] >> b) ^ (t & ((right ? taucw[1] : taucw[0]) >> i))) & 1u;
+            acc += (tau ? leaf : 0u) + sigma;        // out_i, sign applied at the end
+#pragma unroll
+            for (int c = 0; c < 4; c++) child[c] = g[0][c];
+        } else {
+            uint32_t g[1][4];
+            const uint32_t sin[1][4] = { { s[0], s[1], s[2], s[3] } };
+            const uint32_t pk[1] = { pick };
+            aes_mmo<-1>(g, sin, pk, L);
+#pragma unroll
+            for (int c = 0; c < 4; c++) child[c] = g[0][c];
+        }
+        // (s, t) <- state_{x[i]} = G(s) xor t . CW, all gated by the t entering the level
+        const uint32_t t_child = child[0] & 1u;
+        s[0] = (child[0] & ~1u) ^ (scw.x & tm);
+        s[1] = child[1] ^ (scw.y & tm);
+        s[2] = child[2] ^ (scw.z & tm);
+        s[3] = child[3] ^ (scw.w & tm);
+        t = t_child ^ (t & ((right ? tcw[1] : tcw[0]) >> i) & 1u);
+    }
+    acc += (t ? p.last[e] : 0u) + (s[3] & mask);     // out_{n+1}
+    store_share<MODE>(a, e, acc, mask);
+}
+
+// The same walk with four lanes per element (quad layout of aes_quad.h): lane 4q + c owns word c of
+// the element's seed and of its seed-sized correction words; the scalar pieces of the walk (t,
+// sigma, tau, the accumulator) are kept in all four lanes and lane 4q writes the result.
+template <bool CMP, int MODE, bool BALANCE>
+__device__ __forceinline__ void eval_quad_walk(const EvalArgs &a, const EvalPlanes &p, const LaneBase L, const QuadKeys &K,
+                                               size_t e, uint32_t col)
+{
+    const int n = a.n;
+    const uint32_t mask = ring_mask(n);
+    const uint32_t keep = col == 0 ? ~1u : ~0u;           // clears the control bit, which lives in column 0
+    const uint32_t *seed_w = reinterpret_cast<const uint32_t *>(p.seed);
+    const uint32_t *scw_w = reinterpret_cast<const uint32_t *>(p.scw);
+    uint32_t s = seed_w[4 * e + col] & keep;
+    uint32_t t = (uint32_t)a.party;
+    uint32_t tcw[2], taucw[2] = { 0, 0 };
+    if constexpr (CMP) {
+        const uint4 c = reinterpret_cast<const uint4 *>(p.ctrl)[e];
+        tcw[0] = c.x; tcw[1] = c.y; taucw[0] = c.z; taucw[1] = c.w;
+    } else {
+        const uint2 c = reinterpret_cast<const uint2 *>(p.ctrl)[e];
+        tcw[0] = c.x; tcw[1] = c.y;
+    }
+    uint32_t xin = a.x[e];
+    if constexpr (MODE != kPlain) xin += a.x2[e];
+    const uint32_t x = xin & mask;
+    uint32_t acc = 0;
+
+    uint32_t scw_next = scw_w[4 * e + col];
+    uint32_t sig_next = 0, leaf_next = 0;
+    if constexpr (CMP) { sig_next = p.sig[e]; leaf_next = p.leaf[e]; }
+    int next_drop = tile_priority_start(n, BALANCE);
+    for (int i = 0; i < n; i++) {
+        if constexpr (BALANCE) {
+            if (i == next_drop) next_drop = lower_priority(i, n);
+        }
+        const uint32_t scw = scw_next, sigcw = sig_next, leaf = leaf_next;
+        if (i + 1 < n) {
+            const size_t pe = (size_t)(i + 1) * p.bp + e;
+            scw_next = scw_w[4 * pe + col];
+            if constexpr (CMP) { sig_next = p.sig[pe]; leaf_next = p.leaf[pe]; }
+        }
+        const uint32_t b = (x >> (n - 1 - i)) & 1u;
+        const bool right = b != 0;
+        const uint32_t pick = 0u - b;
+        const uint32_t tm = 0u - t;
+        uint32_t child;
+        if constexpr (CMP) {
+            uint32_t g[2];
+            const uint32_t sin[2] = { s, s };
+            aes_mmo_quad<2, -1, 2>(g, sin, pick, K, L);             // G_{1+x[i]}(s) and G_3(s)
+            const uint32_t sigL = quad_broadcast<0>(g[1]), sigR = quad_broadcast<1>(g[1]), w2 = quad_broadcast<2>(g[1]);
+            const uint32_t sigma = ((right ? sigR : sigL) ^ (sigcw & tm)) & mask;
+            const uint32_t tau = ((w2 >> b) ^ (t & ((right ? taucw[1] : taucw[0]) >> i))) & 1u;
+            acc += (tau ? leaf : 0u) + sigma;
+            child = g[0];
+        } else {
+            uint32_t g[1];
+            const uint32_t sin[1] = { s };
+            aes_mmo_quad<0, -1>(g, sin, pick, K, L);
+            child = g[0];
+        }
+        const uint32_t t_child = quad_broadcast<0>(child) & 1u;
+        s = (child & keep) ^ (scw & tm);
+        t = t_child ^ (t & ((right ? tcw[1] : tcw[0]) >> i) & 1u);
+    }
+    acc += (t ? p.last[e] : 0u) + (quad_broadcast<3>(s) & mask);
+    if (col == 0) store_share<MODE>(a, e, acc, mask);
+}
+
+// Batches from the layout switch on.  Elements [0, 64 lane_tiles) are walked one lane per element:
+// the unit of work is a 64-element tile per wavefront, and tile (p W + w) G + g goes to wavefront w
+// of workgroup g in pass p (G workgroups of W wavefronts).  What is left after the last FULL pass
+// would keep only a few wavefronts per CU busy for a whole walk; when it is short, the host hands it
+// over as quad_tiles tiles of 16 elements, walked four lanes per element by the same wavefronts
+// (four times the wavefronts, a quarter of the dependent chain each).
 template <bool CMP, int MODE>
 __global__ __launch_bounds__(kThreads) void eval_kernel(EvalArgs a)
 {
     extern __shared__ uint32_t lds[];
+    const KeyLayout k = key_layout(CMP, a.n, a.batch);
+    const EvalPlanes p = eval_planes(a, k);
+    const uint32_t lane = threadIdx.x & 63u;
+    const size_t stride = (size_t)(blockDim.x >> 6) * gridDim.x;
+    const size_t slot = (size_t)wave_index() * gridDim.x + blockIdx.x;
+
+    // the first tile's inputs are requested before the tables are filled
+    size_t tile = slot;
+    size_t e = tile * 64 + lane;
+    bool live = tile < a.lane_tiles && e < a.batch;
+    LaneInputs<CMP> in = {};
+    if (live) in = load_lane_inputs<CMP, MODE>(a, p, e);
+
     fill_tables(lds);
     __syncthreads();
     const LaneBase L = lane_base(lds);
-    const KeyLayout k = key_layout(CMP, a.n, a.batch);
-    const int n = a.n;
-    const uint32_t mask = ring_mask(n);
-    const uint4 *seed_p = reinterpret_cast<const uint4 *>(a.key + k.seed);
-    const uint4 *scw_p = reinterpret_cast<const uint4 *>(a.key + k.s_cw);
-    const uint32_t *sig_p = reinterpret_cast<const uint32_t *>(a.key + k.sigma_cw);
-    const uint32_t *leaf_p = reinterpret_cast<const uint32_t *>(a.key + k.leaf);
-    const uint32_t *last_p = reinterpret_cast<const uint32_t *>(a.key + k.last);
 
-    // Work unit = a 64-element tile per wavefront.  Tile t of pass p goes to wavefront w of
-    // workgroup g with t = (p * waves_per_group + w) * groups + g, so that a ragged last pass
-    // leaves one busy wavefront on many CUs rather than a few fully loaded CUs.
-    const size_t tiles = (a.batch + 63) / 64;
-    const size_t tile_stride = (size_t)(blockDim.x >> 6) * gridDim.x;
-    for (size_t tile = (size_t)(threadIdx.x >> 6) * gridDim.x + blockIdx.x; tile < tiles; tile += tile_stride) {
-        const size_t e = tile * 64 + (threadIdx.x & 63u);
-        if (e >= a.batch) continue;
-        uint4 sv = seed_p[e];
-        uint32_t s[4] = { sv.x & ~1u, sv.y, sv.z, sv.w };
-        uint32_t t = (uint32_t)a.party;                 // t^(1) = j
-        uint32_t tcw[2], taucw[2] = { 0, 0 };
-        if constexpr (CMP) {
-            uint4 c = reinterpret_cast<const uint4 *>(a.key + k.ctrl)[e];
-            tcw[0] = c.x; tcw[1] = c.y; taucw[0] = c.z; taucw[1] = c.w;
-        } else {
-            uint2 c = reinterpret_cast<const uint2 *>(a.key + k.ctrl)[e];
-            tcw[0] = c.x; tcw[1] = c.y;
-        }
-        uint32_t xin = a.x[e];
-        if constexpr (MODE != kPlain) xin += a.x2[e];    // the reveal: x = alpha + y
-        const uint32_t x = xin & mask;
-        uint32_t acc = 0;
+    while (tile < a.lane_tiles) {
+        // ... and every further tile's while the wavefront walks the one before it
+        const size_t next_tile = tile + stride;
+        const size_t next_e = next_tile * 64 + lane;
+        const bool next_live = next_tile < a.lane_tiles && next_e < a.batch;
+        LaneInputs<CMP> next_in = {};
+        if (next_live) next_in = load_lane_inputs<CMP, MODE>(a, p, next_e);
+        if (live) eval_lane_walk<CMP, MODE>(a, p, L, e, in);
+        tile = next_tile; e = next_e; live = next_live; in = next_in;
+    }
 
-        // correction words are fetched one level ahead of their use
-        uint4 scw_next = scw_p[e];
-        uint32_t sig_next = 0, leaf_next = 0;
-        if constexpr (CMP) { sig_next = sig_p[e]; leaf_next = leaf_p[e]; }
-        int next_drop = tile_priority_start(n, a.balance != 0);
-        for (int i = 0; i < n; i++) {                   // level i + 1
-            if (i == next_drop) next_drop = lower_priority(i, n);
-            const uint4 scw = scw_next;
-            const uint32_t sigcw = sig_next, leaf = leaf_next;
-            if (i + 1 < n) {
-                const size_t pe = (size_t)(i + 1) * k.bp + e;
-                scw_next = scw_p[pe];
-                if constexpr (CMP) { sig_next = sig_p[pe]; leaf_next = leaf_p[pe]; }
-            }
-            const uint32_t b = (x >> (n - 1 - i)) & 1u;  // x[i], most significant first
-            const bool right = b != 0;
-            const uint32_t pick = 0u - b;                // all ones iff x[i] = 1
-            const uint32_t tm = 0u - t;                  // all ones iff t = 1
-
-            uint32_t child[4];
-            if constexpr (CMP) {
-                uint32_t g[2][4];
-                const uint32_t pk[2] = { pick, 0u };
-                aes_mmo_same_input<kNeedSigmaTau, -1, 2>(g, s, pk, L);  // G_{1+x[i]}(s) and G_3(s)
-                const uint32_t sigma = ((right ? g[1][1] : g[1][0]) ^ (sigcw & tm)) & mask;
-                const uint32_t tau = ((g[1][2] >> b) ^ (t & ((right ? taucw[1] : taucw[0]) >> i))) & 1u;
-                acc += (tau ? leaf : 0u) + sigma;        // out_i, sign applied at the end
-#pragma unroll
-                for (int c = 0; c < 4; c++) child[c] = g[0][c];
-            } else {
-                uint32_t g[1][4];
-                const uint32_t in[1][4] = { { s[0], s[1], s[2], s[3] } };
-                const uint32_t pk[1] = { pick };
-                aes_mmo<-1>(g, in, pk, L);
-#pragma unroll
-                for (int c = 0; c < 4; c++) child[c] = g[0][c];
-            }
-            // (s, t) <- state_{x[i]} = G(s) xor t . CW, all gated by the t entering the level
-            const uint32_t t_child = child[0] & 1u;
-            s[0] = (child[0] & ~1u) ^ (scw.x & tm);
-            s[1] = child[1] ^ (scw.y & tm);
-            s[2] = child[2] ^ (scw.z & tm);
-            s[3] = child[3] ^ (scw.w & tm);
-            t = t_child ^ (t & ((right ? tcw[1] : tcw[0]) >> i) & 1u);
-        }
-        acc += (t ? last_p[e] : 0u) + (s[3] & mask);     // out_{n+1}
-        if (a.party) acc = 0u - acc;
-        acc &= mask;
-        if constexpr (MODE == kReluOpen) {
-            const uint32_t v = ((a.party ? 0u : 1u) - acc) & mask;     // share of 1{y > 0}
-            a.out[e] = (a.y_share[e] - a.tri_a[e]) & mask;
-            a.out2[e] = (v - a.tri_b[e]) & mask;
-        } else {
-            a.out[e] = acc;
+    if (a.quad_tiles != 0) {
+        const QuadKeys K = load_quad_keys();
+        const size_t first = a.lane_tiles * 64;
+        // dealt from the first wavefront that has no 64-element tile in the last, partial pass
+        const size_t used = a.lane_tiles % stride;
+        for (size_t q = slot >= used ? slot - used : slot + stride - used; q < a.quad_tiles; q += stride) {
+            const size_t qe = first + q * 16 + (lane >> 2);
+            if (qe < a.batch) eval_quad_walk<CMP, MODE, true>(a, p, L, K, qe, threadIdx.x & 3u);   // whole quads drop out together
         }
     }
 }
 
-// The same evaluation with four lanes per element (quad layout of aes_quad.h): lane 4q + c owns
-// word c of the element's seed and of its seed-sized correction words; the scalar pieces of the
-// walk (t, sigma, tau, the accumulator) are kept in all four lanes and lane 4q writes the result.
-// Used for batches that leave CUs short of wavefronts in the one-lane-per-element layout.
-template <bool CMP, int MODE>
+// Batches below the layout switch: every element four lanes wide, 16-element tiles dealt to
+// wavefronts like the 64-element tiles above.  BALANCE: some SIMD has more than one working wavefront.
+template <bool CMP, int MODE, bool BALANCE>
 __global__ __launch_bounds__(kThreads) void eval_quad_kernel(EvalArgs a)
 {
     extern __shared__ uint32_t lds[];
@@ -199,85 +350,12 @@ __global__ __launch_bounds__(kThreads) void eval_quad_kernel(EvalArgs a)
     const LaneBase L = lane_base(lds);
     const QuadKeys K = load_quad_keys();
     const KeyLayout k = key_layout(CMP, a.n, a.batch);
-    const int n = a.n;
-    const uint32_t mask = ring_mask(n);
-    const uint32_t col = threadIdx.x & 3u;
-    const uint32_t keep = col == 0 ? ~1u : ~0u;           // clears the control bit, which lives in column 0
-    const uint32_t *seed_p = reinterpret_cast<const uint32_t *>(a.key + k.seed);
-    const uint32_t *scw_p = reinterpret_cast<const uint32_t *>(a.key + k.s_cw);
-    const uint32_t *sig_p = reinterpret_cast<const uint32_t *>(a.key + k.sigma_cw);
-    const uint32_t *leaf_p = reinterpret_cast<const uint32_t *>(a.key + k.leaf);
-    const uint32_t *last_p = reinterpret_cast<const uint32_t *>(a.key + k.last);
-
-    // 16-element tiles, dealt to wavefronts like the 64-element tiles of eval_kernel
+    const EvalPlanes p = eval_planes(a, k);
     const size_t tiles = (a.batch + 15) / 16;
-    const size_t tile_stride = (size_t)(blockDim.x >> 6) * gridDim.x;
-    for (size_t tile = (size_t)(threadIdx.x >> 6) * gridDim.x + blockIdx.x; tile < tiles; tile += tile_stride) {
+    const size_t stride = (size_t)(blockDim.x >> 6) * gridDim.x;
+    for (size_t tile = (size_t)wave_index() * gridDim.x + blockIdx.x; tile < tiles; tile += stride) {
         const size_t e = tile * 16 + ((threadIdx.x & 63u) >> 2);
-        if (e >= a.batch) continue;                      // whole quads drop out together
-        uint32_t s = seed_p[4 * e + col] & keep;
-        uint32_t t = (uint32_t)a.party;
-        uint32_t tcw[2], taucw[2] = { 0, 0 };
-        if constexpr (CMP) {
-            uint4 c = reinterpret_cast<const uint4 *>(a.key + k.ctrl)[e];
-            tcw[0] = c.x; tcw[1] = c.y; taucw[0] = c.z; taucw[1] = c.w;
-        } else {
-            uint2 c = reinterpret_cast<const uint2 *>(a.key + k.ctrl)[e];
-            tcw[0] = c.x; tcw[1] = c.y;
-        }
-        uint32_t xin = a.x[e];
-        if constexpr (MODE != kPlain) xin += a.x2[e];
-        const uint32_t x = xin & mask;
-        uint32_t acc = 0;
-
-        uint32_t scw_next = scw_p[4 * e + col];
-        uint32_t sig_next = 0, leaf_next = 0;
-        if constexpr (CMP) { sig_next = sig_p[e]; leaf_next = leaf_p[e]; }
-        int next_drop = tile_priority_start(n, a.balance != 0);
-        for (int i = 0; i < n; i++) {
-            if (i == next_drop) next_drop = lower_priority(i, n);
-            const uint32_t scw = scw_next, sigcw = sig_next, leaf = leaf_next;
-            if (i + 1 < n) {
-                const size_t pe = (size_t)(i + 1) * k.bp + e;
-                scw_next = scw_p[4 * pe + col];
-                if constexpr (CMP) { sig_next = sig_p[pe]; leaf_next = leaf_p[pe]; }
-            }
-            const uint32_t b = (x >> (n - 1 - i)) & 1u;
-            const bool right = b != 0;
-            const uint32_t pick = 0u - b;
-            const uint32_t tm = 0u - t;
-            uint32_t child;
-            if constexpr (CMP) {
-                uint32_t g[2];
-                const uint32_t in[2] = { s, s };
-                aes_mmo_quad<2, -1, 2>(g, in, pick, K, L);             // G_{1+x[i]}(s) and G_3(s)
-                const uint32_t sigL = quad_broadcast<0>(g[1]), sigR = quad_broadcast<1>(g[1]), w2 = quad_broadcast<2>(g[1]);
-                const uint32_t sigma = ((right ? sigR : sigL) ^ (sigcw & tm)) & mask;
-                const uint32_t tau = ((w2 >> b) ^ (t & ((right ? taucw[1] : taucw[0]) >> i))) & 1u;
-                acc += (tau ? leaf : 0u) + sigma;
-                child = g[0];
-            } else {
-                uint32_t g[1];
-                const uint32_t in[1] = { s };
-                aes_mmo_quad<0, -1>(g, in, pick, K, L);
-                child = g[0];
-            }
-            const uint32_t t_child = quad_broadcast<0>(child) & 1u;
-            s = (child & keep) ^ (scw & tm);
-            t = t_child ^ (t & ((right ? tcw[1] : tcw[0]) >> i) & 1u);
-        }
-        acc += (t ? last_p[e] : 0u) + (quad_broadcast<3>(s) & mask);
-        if (a.party) acc = 0u - acc;
-        acc &= mask;
-        if (col == 0) {
-            if constexpr (MODE == kReluOpen) {
-                const uint32_t v = ((a.party ? 0u : 1u) - acc) & mask;
-                a.out[e] = (a.y_share[e] - a.tri_a[e]) & mask;
-                a.out2[e] = (v - a.tri_b[e]) & mask;
-            } else {
-                a.out[e] = acc;
-            }
-        }
+        if (e < a.batch) eval_quad_walk<CMP, MODE, BALANCE>(a, p, L, K, e, threadIdx.x & 3u);
     }
 }
 
@@ -405,6 +483,227 @@ __device__ __forceinline__ void zero_padding_element(uint8_t *key0, uint8_t *key
     }
 }
 
+// KeyGen of one element by one lane.
+template <bool CMP>
+__device__ __forceinline__ void gen_lane_walk(const GenArgs &a, const KeyLayout &k, const LaneBase L, size_t e)
+{
+    const int n = a.n;
+    const uint32_t mask = ring_mask(n);
+    const uint32_t alpha = a.alpha[e] & mask;
+    const uint32_t r = a.alpha_r[e] & mask;
+    uint4 v0 = a.seed0[e], v1 = a.seed1[e];
+    uint32_t s[2][4] = { { v0.x & ~1u, v0.y, v0.z, v0.w }, { v1.x & ~1u, v1.y, v1.z, v1.w } };
+    uint32_t t[2] = { 0u, 1u };                       // t_j^(1) = j
+    uint32_t ctrl[4] = { 0, 0, 0, 0 };
+
+    reinterpret_cast<uint32_t *>(a.key0 + k.alpha_share)[e] = r;
+    reinterpret_cast<uint32_t *>(a.key1 + k.alpha_share)[e] = (alpha - r) & mask;
+    reinterpret_cast<uint4 *>(a.key0 + k.seed)[e] = make_uint4(s[0][0], s[0][1], s[0][2], s[0][3]);
+    reinterpret_cast<uint4 *>(a.key1 + k.seed)[e] = make_uint4(s[1][0], s[1][1], s[1][2], s[1][3]);
+
+    int next_drop = tile_priority_start(n, true);
+    for (int i = 0; i < n; i++) {                     // level i + 1
+        if (i == next_drop) next_drop = lower_priority(i, n);
+        const uint32_t abit = (alpha >> (n - 1 - i)) & 1u;   // alpha[i]; Keep = abit, Lose = 1 - abit
+        uint32_t g[2][3][4];                          // [party][G_1, G_2, G_3][word]
+        if constexpr (CMP) {
+#pragma unroll
+            for (int j = 0; j < 2; j++) {
+                uint32_t h[3][4];
+                const uint32_t pk[3] = { 0, 0, 0 };
+                aes_mmo_same_input<kNeedSigmaTau, 0, 1, 2>(h, s[j], pk, L);
+#pragma unroll
+                for (int m = 0; m < 3; m++)
+#pragma unroll
+                    for (int c = 0; c < 4; c++) g[j][m][c] = h[m][c];
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 2; j++) {
+                uint32_t h[2][4];
+                const uint32_t pk[2] = { 0, 0 };
+                aes_mmo_same_input<kNeedAll, 0, 1>(h, s[j], pk, L);
+#pragma unroll
+                for (int c = 0; c < 4; c++) { g[j][0][c] = h[0][c]; g[j][1][c] = h[1][c]; g[j][2][c] = 0; }
+            }
+        }
+        // control bits of the children, and the children with that bit cleared
+        uint32_t tL[2], tR[2];
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+            tL[j] = g[j][0][0] & 1u; g[j][0][0] &= ~1u;
+            tR[j] = g[j][1][0] & 1u; g[j][1][0] &= ~1u;
+        }
+        const uint32_t km = 0u - abit;               // all ones iff Keep = R
+        // (s,t) part of CW: the Lose-side string, and bits making t_0^t_1 = 1 on Keep, 0 on Lose
+        uint32_t scw[4];
+#pragma unroll
+        for (int c = 0; c < 4; c++)
+            scw[c] = pick32(km, g[0][0][c] ^ g[1][0][c], g[0][1][c] ^ g[1][1][c]);
+        const uint32_t tcwL = tL[0] ^ tL[1] ^ abit ^ 1u;
+        const uint32_t tcwR = tR[0] ^ tR[1] ^ abit;
+        ctrl[0] |= tcwL << i;
+        ctrl[1] |= tcwR << i;
+
+        uint32_t sigcw = 0, leaf = 0;
+        if constexpr (CMP) {
+            // (sigma,tau) part: Keep-side string published, tau_0^tau_1 = 1 on Lose
+            const uint32_t sgL0 = g[0][2][0] & mask, sgR0 = g[0][2][1] & mask;
+            const uint32_t sgL1 = g[1][2][0] & mask, sgR1 = g[1][2][1] & mask;
+            const uint32_t tauL0 = g[0][2][2] & 1u, tauR0 = (g[0][2][2] >> 1) & 1u;
+            const uint32_t tauL1 = g[1][2][2] & 1u, tauR1 = (g[1][2][2] >> 1) & 1u;
+            sigcw = pick32(km, sgR0 ^ sgR1, sgL0 ^ sgL1);
+            const uint32_t taucwL = tauL0 ^ tauL1 ^ abit;
+            const uint32_t taucwR = tauR0 ^ tauR1 ^ abit ^ 1u;
+            ctrl[2] |= taucwL << i;
+            ctrl[3] |= taucwR << i;
+            // state'_{j, Lose}
+            const uint32_t taucw_lose = pick32(km, taucwL, taucwR);
+            const uint32_t sg0 = pick32(km, sgL0, sgR0) ^ (sigcw & (0u - t[0]));
+            const uint32_t sg1 = pick32(km, sgL1, sgR1) ^ (sigcw & (0u - t[1]));
+            const uint32_t tau1 = pick32(km, tauL1, tauR1) ^ (t[1] & taucw_lose);
+            leaf = (abit - sg0 + sg1) & mask;         // (-1)^{tau_1} (alpha[i] - sigma_0 + sigma_1)
+            leaf = ((leaf ^ (0u - tau1)) + tau1) & mask;   // negate iff tau_1 = 1
+        }
+        // both parties move to state_{j, Keep}, corrected with the OLD t_j
+        const uint32_t tcw_keep = pick32(km, tcwR, tcwL);
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+            const uint32_t tm = 0u - t[j];
+#pragma unroll
+            for (int c = 0; c < 4; c++)
+                s[j][c] = pick32(km, g[j][1][c], g[j][0][c]) ^ (scw[c] & tm);
+            t[j] = pick32(km, tR[j], tL[j]) ^ (t[j] & tcw_keep);
+        }
+        const size_t pe = (size_t)i * k.bp + e;
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+            reinterpret_cast<uint4 *>((j == 0 ? a.key0 : a.key1) + k.s_cw)[pe] = make_uint4(scw[0], scw[1], scw[2], scw[3]);
+            if constexpr (CMP) {
+                reinterpret_cast<uint32_t *>((j == 0 ? a.key0 : a.key1) + k.sigma_cw)[pe] = sigcw;
+                reinterpret_cast<uint32_t *>((j == 0 ? a.key0 : a.key1) + k.leaf)[pe] = leaf;
+            }
+        }
+    }
+    // CW^(n+1) = (-1)^{t_1} (1 - conv(s_0) + conv(s_1))
+    uint32_t last = (1u - (s[0][3] & mask) + (s[1][3] & mask)) & mask;
+    if (t[1]) last = (0u - last) & mask;
+#pragma unroll
+    for (int j = 0; j < 2; j++) {
+        reinterpret_cast<uint32_t *>((j == 0 ? a.key0 : a.key1) + k.last)[e] = last;
+        if constexpr (CMP) reinterpret_cast<uint4 *>((j == 0 ? a.key0 : a.key1) + k.ctrl)[e] = make_uint4(ctrl[0], ctrl[1], ctrl[2], ctrl[3]);
+        else reinterpret_cast<uint2 *>((j == 0 ? a.key0 : a.key1) + k.ctrl)[e] = make_uint2(ctrl[0], ctrl[1]);
+    }
+}
+
+// KeyGen with four lanes per key pair (quad layout of aes_quad.h): lane 4q + c owns word c of
+// both parties' seeds and of the seed-sized correction word; all six PRG blocks of a level (three
+// per party) are in flight together.
+template <bool CMP, bool BALANCE>
+__device__ __forceinline__ void gen_quad_walk(const GenArgs &a, const KeyLayout &k, const LaneBase L, const QuadKeys &K, size_t e,
+                                              uint32_t col)
+{
+    const int n = a.n;
+    const uint32_t mask = ring_mask(n);
+    const uint32_t keep = col == 0 ? ~1u : ~0u;
+    uint8_t *const my_key = (col & 1u) ? a.key1 : a.key0;   // scalar planes: lanes 0,2 write k_0, lanes 1,3 write k_1
+    const uint32_t *seed0_w = reinterpret_cast<const uint32_t *>(a.seed0);
+    const uint32_t *seed1_w = reinterpret_cast<const uint32_t *>(a.seed1);
+    const uint32_t alpha = a.alpha[e] & mask;
+    const uint32_t r = a.alpha_r[e] & mask;
+    uint32_t s[2] = { seed0_w[4 * e + col] & keep, seed1_w[4 * e + col] & keep };
+    uint32_t t[2] = { 0u, 1u };
+    uint32_t ctrl[4] = { 0, 0, 0, 0 };
+    reinterpret_cast<uint32_t *>(a.key0 + k.seed)[4 * e + col] = s[0];
+    reinterpret_cast<uint32_t *>(a.key1 + k.seed)[4 * e + col] = s[1];
+
+    int next_drop = tile_priority_start(n, BALANCE);
+    for (int i = 0; i < n; i++) {
+        if constexpr (BALANCE) {
+            if (i == next_drop) next_drop = lower_priority(i, n);
+        }
+        const uint32_t abit = (alpha >> (n - 1 - i)) & 1u;
+        uint32_t g[2][3];                             // [party][G_1, G_2, G_3], this lane's column
+        if constexpr (CMP) {
+            uint32_t h[6];
+            const uint32_t in[6] = { s[0], s[0], s[0], s[1], s[1], s[1] };
+            aes_mmo_quad<3, 0, 1, 2, 0, 1, 2>(h, in, 0u, K, L);
+#pragma unroll
+            for (int j = 0; j < 2; j++)
+#pragma unroll
+                for (int m = 0; m < 3; m++) g[j][m] = h[3 * j + m];
+        } else {
+            uint32_t h[4];
+            const uint32_t in[4] = { s[0], s[0], s[1], s[1] };
+            aes_mmo_quad<2, 0, 1, 0, 1>(h, in, 0u, K, L);
+#pragma unroll
+            for (int j = 0; j < 2; j++) { g[j][0] = h[2 * j]; g[j][1] = h[2 * j + 1]; g[j][2] = 0; }
+        }
+        uint32_t tL[2], tR[2];
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+            tL[j] = quad_broadcast<0>(g[j][0]) & 1u; g[j][0] &= keep;
+            tR[j] = quad_broadcast<0>(g[j][1]) & 1u; g[j][1] &= keep;
+        }
+        const uint32_t km = 0u - abit;
+        const uint32_t scw = pick32(km, g[0][0] ^ g[1][0], g[0][1] ^ g[1][1]);
+        const uint32_t tcwL = tL[0] ^ tL[1] ^ abit ^ 1u;
+        const uint32_t tcwR = tR[0] ^ tR[1] ^ abit;
+        ctrl[0] |= tcwL << i;
+        ctrl[1] |= tcwR << i;
+
+        uint32_t sigcw = 0, leaf = 0;
+        if constexpr (CMP) {
+            const uint32_t sgL0 = quad_broadcast<0>(g[0][2]) & mask, sgR0 = quad_broadcast<1>(g[0][2]) & mask;
+            const uint32_t sgL1 = quad_broadcast<0>(g[1][2]) & mask, sgR1 = quad_broadcast<1>(g[1][2]) & mask;
+            const uint32_t w0 = quad_broadcast<2>(g[0][2]), w1 = quad_broadcast<2>(g[1][2]);
+            const uint32_t tauL0 = w0 & 1u, tauR0 = (w0 >> 1) & 1u;
+            const uint32_t tauL1 = w1 & 1u, tauR1 = (w1 >> 1) & 1u;
+            sigcw = pick32(km, sgR0 ^ sgR1, sgL0 ^ sgL1);
+            const uint32_t taucwL = tauL0 ^ tauL1 ^ abit;
+            const uint32_t taucwR = tauR0 ^ tauR1 ^ abit ^ 1u;
+            ctrl[2] |= taucwL << i;
+            ctrl[3] |= taucwR << i;
+            const uint32_t taucw_lose = pick32(km, taucwL, taucwR);
+            const uint32_t sg0 = pick32(km, sgL0, sgR0) ^ (sigcw & (0u - t[0]));
+            const uint32_t sg1 = pick32(km, sgL1, sgR1) ^ (sigcw & (0u - t[1]));
+            const uint32_t tau1 = pick32(km, tauL1, tauR1) ^ (t[1] & taucw_lose);
+            leaf = (abit - sg0 + sg1) & mask;
+            leaf = ((leaf ^ (0u - tau1)) + tau1) & mask;
+        }
+        const uint32_t tcw_keep = pick32(km, tcwR, tcwL);
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+            s[j] = pick32(km, g[j][1], g[j][0]) ^ (scw & (0u - t[j]));
+            t[j] = pick32(km, tR[j], tL[j]) ^ (t[j] & tcw_keep);
+        }
+        const size_t pe = (size_t)i * k.bp + e;
+        reinterpret_cast<uint32_t *>(a.key0 + k.s_cw)[4 * pe + col] = scw;
+        reinterpret_cast<uint32_t *>(a.key1 + k.s_cw)[4 * pe + col] = scw;
+        if constexpr (CMP) {
+            // one store for the four scalar words: lanes 0,1 sigma_CW of k_0, k_1; lanes 2,3 CW_leaf of k_0, k_1
+            reinterpret_cast<uint32_t *>(my_key + ((col & 2u) ? k.leaf : k.sigma_cw))[pe] = (col & 2u) ? leaf : sigcw;
+        }
+    }
+    const uint32_t c0 = quad_broadcast<3>(s[0]) & mask, c1 = quad_broadcast<3>(s[1]) & mask;
+    uint32_t last = (1u - c0 + c1) & mask;
+    if (t[1]) last = (0u - last) & mask;
+    // lanes 0,1: [[alpha]]_0, [[alpha]]_1; lanes 2,3: CW^(n+1) of k_0, k_1
+    const uint32_t share = (col & 1u) ? ((alpha - r) & mask) : r;
+    reinterpret_cast<uint32_t *>(my_key + ((col & 2u) ? k.last : k.alpha_share))[e] = (col & 2u) ? last : share;
+    if constexpr (CMP) {
+        const uint32_t cw = col == 0 ? ctrl[0] : col == 1 ? ctrl[1] : col == 2 ? ctrl[2] : ctrl[3];
+        reinterpret_cast<uint32_t *>(a.key0 + k.ctrl)[4 * e + col] = cw;
+        reinterpret_cast<uint32_t *>(a.key1 + k.ctrl)[4 * e + col] = cw;
+    } else if (col < 2) {
+        const uint32_t cw = col == 0 ? ctrl[0] : ctrl[1];
+        reinterpret_cast<uint32_t *>(a.key0 + k.ctrl)[2 * e + col] = cw;
+        reinterpret_cast<uint32_t *>(a.key1 + k.ctrl)[2 * e + col] = cw;
+    }
+}
+
+// Batches from the layout switch on: the same split of the work as eval_kernel.  The 16-element
+// tiles run to the end of the PADDED batch, so that the padding elements are written too.
 template <bool CMP>
 __global__ __launch_bounds__(kThreads) void gen_kernel(GenArgs a)
 {
@@ -413,130 +712,29 @@ __global__ __launch_bounds__(kThreads) void gen_kernel(GenArgs a)
     __syncthreads();
     const LaneBase L = lane_base(lds);
     const KeyLayout k = key_layout(CMP, a.n, a.batch);
-    const int n = a.n;
-    const uint32_t mask = ring_mask(n);
-
-    // same tile-to-wavefront assignment as the evaluation kernel; the padded batch is whole tiles
-    const size_t tiles = k.bp / 64;
-    const size_t tile_stride = (size_t)(blockDim.x >> 6) * gridDim.x;
-    for (size_t tile = (size_t)(threadIdx.x >> 6) * gridDim.x + blockIdx.x; tile < tiles; tile += tile_stride) {
-        const size_t e = tile * 64 + (threadIdx.x & 63u);
-        if (e >= a.batch) {
-            zero_padding_element<CMP>(a.key0, a.key1, k, e, n);
-            continue;
-        }
-        const uint32_t alpha = a.alpha[e] & mask;
-        const uint32_t r = a.alpha_r[e] & mask;
-        uint4 v0 = a.seed0[e], v1 = a.seed1[e];
-        uint32_t s[2][4] = { { v0.x & ~1u, v0.y, v0.z, v0.w }, { v1.x & ~1u, v1.y, v1.z, v1.w } };
-        uint32_t t[2] = { 0u, 1u };                       // t_j^(1) = j
-        uint32_t ctrl[4] = { 0, 0, 0, 0 };
-
-        reinterpret_cast<uint32_t *>(a.key0 + k.alpha_share)[e] = r;
-        reinterpret_cast<uint32_t *>(a.key1 + k.alpha_share)[e] = (alpha - r) & mask;
-        reinterpret_cast<uint4 *>(a.key0 + k.seed)[e] = make_uint4(s[0][0], s[0][1], s[0][2], s[0][3]);
-        reinterpret_cast<uint4 *>(a.key1 + k.seed)[e] = make_uint4(s[1][0], s[1][1], s[1][2], s[1][3]);
-
-        int next_drop = tile_priority_start(n, a.balance != 0);
-        for (int i = 0; i < n; i++) {                     // level i + 1
-            if (i == next_drop) next_drop = lower_priority(i, n);
-            const uint32_t abit = (alpha >> (n - 1 - i)) & 1u;   // alpha[i]; Keep = abit, Lose = 1 - abit
-            uint32_t g[2][3][4];                          // [party][G_1, G_2, G_3][word]
-            if constexpr (CMP) {
-#pragma unroll
-                for (int j = 0; j < 2; j++) {
-                    uint32_t h[3][4];
-                    const uint32_t pk[3] = { 0, 0, 0 };
-                    aes_mmo_same_input<kNeedSigmaTau, 0, 1, 2>(h, s[j], pk, L);
-#pragma unroll
-                    for (int m = 0; m < 3; m++)
-#pragma unroll
-                        for (int c = 0; c < 4; c++) g[j][m][c] = h[m][c];
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < 2; j++) {
-                    uint32_t h[2][4];
-                    const uint32_t pk[2] = { 0, 0 };
-                    aes_mmo_same_input<kNeedAll, 0, 1>(h, s[j], pk, L);
-#pragma unroll
-                    for (int c = 0; c < 4; c++) { g[j][0][c] = h[0][c]; g[j][1][c] = h[1][c]; g[j][2][c] = 0; }
-                }
-            }
-            // control bits of the children, and the children with that bit cleared
-            uint32_t tL[2], tR[2];
-#pragma unroll
-            for (int j = 0; j < 2; j++) {
-                tL[j] = g[j][0][0] & 1u; g[j][0][0] &= ~1u;
-                tR[j] = g[j][1][0] & 1u; g[j][1][0] &= ~1u;
-            }
-            const uint32_t km = 0u - abit;               // all ones iff Keep = R
-            // (s,t) part of CW: the Lose-side string, and bits making t_0^t_1 = 1 on Keep, 0 on Lose
-            uint32_t scw[4];
-#pragma unroll
-            for (int c = 0; c < 4; c++)
-                scw[c] = pick32(km, g[0][0][c] ^ g[1][0][c], g[0][1][c] ^ g[1][1][c]);
-            const uint32_t tcwL = tL[0] ^ tL[1] ^ abit ^ 1u;
-            const uint32_t tcwR = tR[0] ^ tR[1] ^ abit;
-            ctrl[0] |= tcwL << i;
-            ctrl[1] |= tcwR << i;
-
-            uint32_t sigcw = 0, leaf = 0;
-            if constexpr (CMP) {
-                // (sigma,tau) part: Keep-side string published, tau_0^tau_1 = 1 on Lose
-                const uint32_t sgL0 = g[0][2][0] & mask, sgR0 = g[0][2][1] & mask;
-                const uint32_t sgL1 = g[1][2][0] & mask, sgR1 = g[1][2][1] & mask;
-                const uint32_t tauL0 = g[0][2][2] & 1u, tauR0 = (g[0][2][2] >> 1) & 1u;
-                const uint32_t tauL1 = g[1][2][2] & 1u, tauR1 = (g[1][2][2] >> 1) & 1u;
-                sigcw = pick32(km, sgR0 ^ sgR1, sgL0 ^ sgL1);
-                const uint32_t taucwL = tauL0 ^ tauL1 ^ abit;
-                const uint32_t taucwR = tauR0 ^ tauR1 ^ abit ^ 1u;
-                ctrl[2] |= taucwL << i;
-                ctrl[3] |= taucwR << i;
-                // state'_{j, Lose}
-                const uint32_t taucw_lose = pick32(km, taucwL, taucwR);
-                const uint32_t sg0 = pick32(km, sgL0, sgR0) ^ (sigcw & (0u - t[0]));
-                const uint32_t sg1 = pick32(km, sgL1, sgR1) ^ (sigcw & (0u - t[1]));
-                const uint32_t tau1 = pick32(km, tauL1, tauR1) ^ (t[1] & taucw_lose);
-                leaf = (abit - sg0 + sg1) & mask;         // (-1)^{tau_1} (alpha[i] - sigma_0 + sigma_1)
-                leaf = ((leaf ^ (0u - tau1)) + tau1) & mask;   // negate iff tau_1 = 1
-            }
-            // both parties move to state_{j, Keep}, corrected with the OLD t_j
-            const uint32_t tcw_keep = pick32(km, tcwR, tcwL);
-#pragma unroll
-            for (int j = 0; j < 2; j++) {
-                const uint32_t tm = 0u - t[j];
-#pragma unroll
-                for (int c = 0; c < 4; c++)
-                    s[j][c] = pick32(km, g[j][1][c], g[j][0][c]) ^ (scw[c] & tm);
-                t[j] = pick32(km, tR[j], tL[j]) ^ (t[j] & tcw_keep);
-            }
-            const size_t pe = (size_t)i * k.bp + e;
-#pragma unroll
-            for (int j = 0; j < 2; j++) {
-                reinterpret_cast<uint4 *>((j == 0 ? a.key0 : a.key1) + k.s_cw)[pe] = make_uint4(scw[0], scw[1], scw[2], scw[3]);
-                if constexpr (CMP) {
-                    reinterpret_cast<uint32_t *>((j == 0 ? a.key0 : a.key1) + k.sigma_cw)[pe] = sigcw;
-                    reinterpret_cast<uint32_t *>((j == 0 ? a.key0 : a.key1) + k.leaf)[pe] = leaf;
-                }
-            }
-        }
-        // CW^(n+1) = (-1)^{t_1} (1 - conv(s_0) + conv(s_1))
-        uint32_t last = (1u - (s[0][3] & mask) + (s[1][3] & mask)) & mask;
-        if (t[1]) last = (0u - last) & mask;
-#pragma unroll
-        for (int j = 0; j < 2; j++) {
-            reinterpret_cast<uint32_t *>((j == 0 ? a.key0 : a.key1) + k.last)[e] = last;
-            if constexpr (CMP) reinterpret_cast<uint4 *>((j == 0 ? a.key0 : a.key1) + k.ctrl)[e] = make_uint4(ctrl[0], ctrl[1], ctrl[2], ctrl[3]);
-            else reinterpret_cast<uint2 *>((j == 0 ? a.key0 : a.key1) + k.ctrl)[e] = make_uint2(ctrl[0], ctrl[1]);
+    const uint32_t lane = threadIdx.x & 63u;
+    const size_t stride = (size_t)(blockDim.x >> 6) * gridDim.x;
+    const size_t slot = (size_t)wave_index() * gridDim.x + blockIdx.x;
+    for (size_t tile = slot; tile < a.lane_tiles; tile += stride) {
+        const size_t e = tile * 64 + lane;
+        if (e < a.batch) gen_lane_walk<CMP>(a, k, L, e);
+        else zero_padding_element<CMP>(a.key0, a.key1, k, e, a.n);
+    }
+    if (a.quad_tiles != 0) {
+        const QuadKeys K = load_quad_keys();
+        const size_t first = a.lane_tiles * 64;
+        const size_t used = a.lane_tiles % stride;
+        const uint32_t col = threadIdx.x & 3u;
+        for (size_t q = slot >= used ? slot - used : slot + stride - used; q < a.quad_tiles; q += stride) {
+            const size_t e = first + q * 16 + (lane >> 2);
+            if (e < a.batch) gen_quad_walk<CMP, true>(a, k, L, K, e, col);
+            else if (col == 0) zero_padding_element<CMP>(a.key0, a.key1, k, e, a.n);
         }
     }
 }
 
-// KeyGen with four lanes per key pair (quad layout of aes_quad.h): lane 4q + c owns word c of
-// both parties' seeds and of the seed-sized correction word; all six PRG blocks of a level (three
-// per party) are in flight together.
-template <bool CMP>
+// Batches below the layout switch: every key pair four lanes wide.
+template <bool CMP, bool BALANCE>
 __global__ __launch_bounds__(kThreads) void gen_quad_kernel(GenArgs a)
 {
     extern __shared__ uint32_t lds[];
@@ -545,111 +743,13 @@ __global__ __launch_bounds__(kThreads) void gen_quad_kernel(GenArgs a)
     const LaneBase L = lane_base(lds);
     const QuadKeys K = load_quad_keys();
     const KeyLayout k = key_layout(CMP, a.n, a.batch);
-    const int n = a.n;
-    const uint32_t mask = ring_mask(n);
     const uint32_t col = threadIdx.x & 3u;
-    const uint32_t keep = col == 0 ? ~1u : ~0u;
-    uint8_t *const my_key = (col & 1u) ? a.key1 : a.key0;   // scalar planes: lanes 0,2 write k_0, lanes 1,3 write k_1
-    const uint32_t *seed0_w = reinterpret_cast<const uint32_t *>(a.seed0);
-    const uint32_t *seed1_w = reinterpret_cast<const uint32_t *>(a.seed1);
-
     const size_t tiles = k.bp / 16;
-    const size_t tile_stride = (size_t)(blockDim.x >> 6) * gridDim.x;
-    for (size_t tile = (size_t)(threadIdx.x >> 6) * gridDim.x + blockIdx.x; tile < tiles; tile += tile_stride) {
+    const size_t stride = (size_t)(blockDim.x >> 6) * gridDim.x;
+    for (size_t tile = (size_t)wave_index() * gridDim.x + blockIdx.x; tile < tiles; tile += stride) {
         const size_t e = tile * 16 + ((threadIdx.x & 63u) >> 2);
-        if (e >= a.batch) {
-            if (col == 0) zero_padding_element<CMP>(a.key0, a.key1, k, e, n);
-            continue;
-        }
-        const uint32_t alpha = a.alpha[e] & mask;
-        const uint32_t r = a.alpha_r[e] & mask;
-        uint32_t s[2] = { seed0_w[4 * e + col] & keep, seed1_w[4 * e + col] & keep };
-        uint32_t t[2] = { 0u, 1u };
-        uint32_t ctrl[4] = { 0, 0, 0, 0 };
-        reinterpret_cast<uint32_t *>(a.key0 + k.seed)[4 * e + col] = s[0];
-        reinterpret_cast<uint32_t *>(a.key1 + k.seed)[4 * e + col] = s[1];
-
-        int next_drop = tile_priority_start(n, a.balance != 0);
-        for (int i = 0; i < n; i++) {
-            if (i == next_drop) next_drop = lower_priority(i, n);
-            const uint32_t abit = (alpha >> (n - 1 - i)) & 1u;
-            uint32_t g[2][3];                             // [party][G_1, G_2, G_3], this lane's column
-            if constexpr (CMP) {
-                uint32_t h[6];
-                const uint32_t in[6] = { s[0], s[0], s[0], s[1], s[1], s[1] };
-                aes_mmo_quad<3, 0, 1, 2, 0, 1, 2>(h, in, 0u, K, L);
-#pragma unroll
-                for (int j = 0; j < 2; j++)
-#pragma unroll
-                    for (int m = 0; m < 3; m++) g[j][m] = h[3 * j + m];
-            } else {
-                uint32_t h[4];
-                const uint32_t in[4] = { s[0], s[0], s[1], s[1] };
-                aes_mmo_quad<2, 0, 1, 0, 1>(h, in, 0u, K, L);
-#pragma unroll
-                for (int j = 0; j < 2; j++) { g[j][0] = h[2 * j]; g[j][1] = h[2 * j + 1]; g[j][2] = 0; }
-            }
-            uint32_t tL[2], tR[2];
-#pragma unroll
-            for (int j = 0; j < 2; j++) {
-                tL[j] = quad_broadcast<0>(g[j][0]) & 1u; g[j][0] &= keep;
-                tR[j] = quad_broadcast<0>(g[j][1]) & 1u; g[j][1] &= keep;
-            }
-            const uint32_t km = 0u - abit;
-            const uint32_t scw = pick32(km, g[0][0] ^ g[1][0], g[0][1] ^ g[1][1]);
-            const uint32_t tcwL = tL[0] ^ tL[1] ^ abit ^ 1u;
-            const uint32_t tcwR = tR[0] ^ tR[1] ^ abit;
-            ctrl[0] |= tcwL << i;
-            ctrl[1] |= tcwR << i;
-
-            uint32_t sigcw = 0, leaf = 0;
-            if constexpr (CMP) {
-                const uint32_t sgL0 = quad_broadcast<0>(g[0][2]) & mask, sgR0 = quad_broadcast<1>(g[0][2]) & mask;
-                const uint32_t sgL1 = quad_broadcast<0>(g[1][2]) & mask, sgR1 = quad_broadcast<1>(g[1][2]) & mask;
-                const uint32_t w0 = quad_broadcast<2>(g[0][2]), w1 = quad_broadcast<2>(g[1][2]);
-                const uint32_t tauL0 = w0 & 1u, tauR0 = (w0 >> 1) & 1u;
-                const uint32_t tauL1 = w1 & 1u, tauR1 = (w1 >> 1) & 1u;
-                sigcw = pick32(km, sgR0 ^ sgR1, sgL0 ^ sgL1);
-                const uint32_t taucwL = tauL0 ^ tauL1 ^ abit;
-                const uint32_t taucwR = tauR0 ^ tauR1 ^ abit ^ 1u;
-                ctrl[2] |= taucwL << i;
-                ctrl[3] |= taucwR << i;
-                const uint32_t taucw_lose = pick32(km, taucwL, taucwR);
-                const uint32_t sg0 = pick32(km, sgL0, sgR0) ^ (sigcw & (0u - t[0]));
-                const uint32_t sg1 = pick32(km, sgL1, sgR1) ^ (sigcw & (0u - t[1]));
-                const uint32_t tau1 = pick32(km, tauL1, tauR1) ^ (t[1] & taucw_lose);
-                leaf = (abit - sg0 + sg1) & mask;
-                leaf = ((leaf ^ (0u - tau1)) + tau1) & mask;
-            }
-            const uint32_t tcw_keep = pick32(km, tcwR, tcwL);
-#pragma unroll
-            for (int j = 0; j < 2; j++) {
-                s[j] = pick32(km, g[j][1], g[j][0]) ^ (scw & (0u - t[j]));
-                t[j] = pick32(km, tR[j], tL[j]) ^ (t[j] & tcw_keep);
-            }
-            const size_t pe = (size_t)i * k.bp + e;
-            reinterpret_cast<uint32_t *>(a.key0 + k.s_cw)[4 * pe + col] = scw;
-            reinterpret_cast<uint32_t *>(a.key1 + k.s_cw)[4 * pe + col] = scw;
-            if constexpr (CMP) {
-                // one store for the four scalar words: lanes 0,1 sigma_CW of k_0, k_1; lanes 2,3 CW_leaf of k_0, k_1
-                reinterpret_cast<uint32_t *>(my_key + ((col & 2u) ? k.leaf : k.sigma_cw))[pe] = (col & 2u) ? leaf : sigcw;
-            }
-        }
-        const uint32_t c0 = quad_broadcast<3>(s[0]) & mask, c1 = quad_broadcast<3>(s[1]) & mask;
-        uint32_t last = (1u - c0 + c1) & mask;
-        if (t[1]) last = (0u - last) & mask;
-        // lanes 0,1: [[alpha]]_0, [[alpha]]_1; lanes 2,3: CW^(n+1) of k_0, k_1
-        const uint32_t share = (col & 1u) ? ((alpha - r) & mask) : r;
-        reinterpret_cast<uint32_t *>(my_key + ((col & 2u) ? k.last : k.alpha_share))[e] = (col & 2u) ? last : share;
-        if constexpr (CMP) {
-            const uint32_t cw = col == 0 ? ctrl[0] : col == 1 ? ctrl[1] : col == 2 ? ctrl[2] : ctrl[3];
-            reinterpret_cast<uint32_t *>(a.key0 + k.ctrl)[4 * e + col] = cw;
-            reinterpret_cast<uint32_t *>(a.key1 + k.ctrl)[4 * e + col] = cw;
-        } else if (col < 2) {
-            const uint32_t cw = col == 0 ? ctrl[0] : ctrl[1];
-            reinterpret_cast<uint32_t *>(a.key0 + k.ctrl)[2 * e + col] = cw;
-            reinterpret_cast<uint32_t *>(a.key1 + k.ctrl)[2 * e + col] = cw;
-        }
+        if (e < a.batch) gen_quad_walk<CMP, BALANCE>(a, k, L, K, e, col);
+        else if (col == 0) zero_padding_element<CMP>(a.key0, a.key1, k, e, a.n);
     }
 }
 
@@ -683,11 +783,15 @@ static int prepare_device(DeviceInfo *info)
         const void *fns[] = { (const void *)eval_kernel<true, kPlain>, (const void *)eval_kernel<false, kPlain>,
                               (const void *)eval_kernel<true, kSign>, (const void *)eval_kernel<true, kReluOpen>,
                               (const void *)eval_kernel<false, kSign>,
-                              (const void *)eval_quad_kernel<true, kPlain>, (const void *)eval_quad_kernel<false, kPlain>,
-                              (const void *)eval_quad_kernel<true, kSign>, (const void *)eval_quad_kernel<true, kReluOpen>,
-                              (const void *)eval_quad_kernel<false, kSign>,
+                              (const void *)eval_quad_kernel<true, kPlain, true>, (const void *)eval_quad_kernel<false, kPlain, true>,
+                              (const void *)eval_quad_kernel<true, kSign, true>, (const void *)eval_quad_kernel<true, kReluOpen, true>,
+                              (const void *)eval_quad_kernel<false, kSign, true>,
+                              (const void *)eval_quad_kernel<true, kPlain, false>, (const void *)eval_quad_kernel<false, kPlain, false>,
+                              (const void *)eval_quad_kernel<true, kSign, false>, (const void *)eval_quad_kernel<true, kReluOpen, false>,
+                              (const void *)eval_quad_kernel<false, kSign, false>,
                               (const void *)gen_kernel<true>, (const void *)gen_kernel<false>,
-                              (const void *)gen_quad_kernel<true>, (const void *)gen_quad_kernel<false> };
+                              (const void *)gen_quad_kernel<true, true>, (const void *)gen_quad_kernel<false, true>,
+                              (const void *)gen_quad_kernel<true, false>, (const void *)gen_quad_kernel<false, false> };
         for (size_t i = 0; i < sizeof(fns) / sizeof(fns[0]); i++) {
             err = hipFuncSetAttribute(fns[i], hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
             if (err != hipSuccess) { g_last_hip_error = (int)err; return FSS_ELAUNCH; }
@@ -738,7 +842,10 @@ static LaunchShape shape_for(size_t elems, const DeviceInfo &d, size_t tile_elem
 // wavefronts with one lane per element.  Measured on MI355X, for KeyGen and Eval, comparison and
 // equality alike: the quad layout is faster below about 8 wavefronts of 64 elements per CU (2.1x
 // for Eval and 2.2x for KeyGen at 16,384 elements), slower above (by 25-30 % on large batches).
-constexpr size_t kQuadBelowWavesPerCu = 8;
+#ifndef FSS_QUAD_BELOW
+#define FSS_QUAD_BELOW 8
+#endif
+constexpr size_t kQuadBelowWavesPerCu = FSS_QUAD_BELOW;
 
 static size_t quad_layout_below(const DeviceInfo &d) { return (size_t)d.cus * 64 * kQuadBelowWavesPerCu; }
 
@@ -757,6 +864,56 @@ static int launch(void (*kernel)(P...), unsigned grid, unsigned threads, size_t 
     const hipError_t err = hipLaunchKernel(reinterpret_cast<const void *>(kernel), dim3(grid), dim3(threads), ptrs, lds_bytes, st);
     if (err != hipSuccess) { g_last_hip_error = (int)err; return FSS_ELAUNCH; }
     return FSS_OK;
+}
+
+// How a batch at or above the layout switch is walked.  Tiles of 64 elements, one lane per element,
+// are dealt in rows of one tile per workgroup; 16 rows make a full pass.  Whole rows stay in that
+// layout, except that a short rest after the last full pass (fewer than kQuadTailBelowWavesPerCu
+// rows) is better off four lanes per element, and so is the last, partial row, which would give
+// some CUs one wavefront more than the others (a fourth on one SIMD where the others have three
+// costs the launch as much as a whole row).  Those elements become 16-element tiles at the end of
+// the same launch (see eval_kernel).
+struct WorkSplit {
+    size_t lane_tiles, quad_tiles;
+};
+
+#ifndef FSS_QUAD_TAIL_BELOW
+#define FSS_QUAD_TAIL_BELOW 8
+#endif
+constexpr size_t kQuadTailBelowWavesPerCu = FSS_QUAD_TAIL_BELOW;
+
+static WorkSplit split_work(size_t batch, const LaunchShape &ls)
+{
+    const size_t tiles = batch / 64;                               // whole tiles; a ragged end joins the rest below
+    const size_t row = ls.grid, per_pass = row * (ls.threads / 64);
+    const size_t full = tiles / per_pass * per_pass;
+    const size_t rows_left = (tiles - full) / row;
+    WorkSplit w;
+    w.lane_tiles = full + (full > 0 && rows_left < kQuadTailBelowWavesPerCu ? 0 : rows_left * row);
+    w.quad_tiles = (batch - w.lane_tiles * 64 + 15) / 16;
+    return w;
+}
+
+typedef void (*EvalKernel)(EvalArgs);
+
+static EvalKernel pick_eval_kernel(bool cmp, int mode)
+{
+    if (!cmp) return mode == kPlain ? eval_kernel<false, kPlain> : eval_kernel<false, kSign>;
+    return mode == kPlain ? eval_kernel<true, kPlain> : mode == kSign ? eval_kernel<true, kSign> : eval_kernel<true, kReluOpen>;
+}
+
+template <bool BALANCE>
+static EvalKernel pick_eval_quad_kernel_b(bool cmp, int mode)
+{
+    if (!cmp) return mode == kPlain ? eval_quad_kernel<false, kPlain, BALANCE> : eval_quad_kernel<false, kSign, BALANCE>;
+    return mode == kPlain ? eval_quad_kernel<true, kPlain, BALANCE>
+         : mode == kSign  ? eval_quad_kernel<true, kSign, BALANCE>
+                          : eval_quad_kernel<true, kReluOpen, BALANCE>;
+}
+
+static EvalKernel pick_eval_quad_kernel(bool cmp, int mode, bool balance)
+{
+    return balance ? pick_eval_quad_kernel_b<true>(cmp, mode) : pick_eval_quad_kernel_b<false>(cmp, mode);
 }
 
 static int gen_common(bool cmp, int n, size_t batch, const uint32_t *d_alpha, const uint32_t *d_alpha_r,
@@ -780,13 +937,17 @@ static int gen_common(bool cmp, int n, size_t batch, const uint32_t *d_alpha, co
     a.key0 = static_cast<uint8_t *>(d_key0); a.key1 = static_cast<uint8_t *>(d_key1);
     a.batch = batch; a.n = n;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    a.lane_tiles = 0; a.quad_tiles = 0;
     if (use_quad_layout(batch, dev)) {
         const LaunchShape ls = shape_for(padded_batch(batch), dev, 16);
-        a.balance = ls.balance;
-        return launch(cmp ? gen_quad_kernel<true> : gen_quad_kernel<false>, ls.grid, ls.threads, kLdsBytes, st, a);
+        void (*kernel)(GenArgs) = ls.balance ? (cmp ? gen_quad_kernel<true, true> : gen_quad_kernel<false, true>)
+                                             : (cmp ? gen_quad_kernel<true, false> : gen_quad_kernel<false, false>);
+        return launch(kernel, ls.grid, ls.threads, kLdsBytes, st, a);
     }
-    const LaunchShape ls = shape_for(padded_batch(batch), dev);
-    a.balance = ls.balance;
+    const LaunchShape ls = shape_for(batch, dev);
+    const WorkSplit w = split_work(batch, ls);
+    a.lane_tiles = w.lane_tiles;
+    a.quad_tiles = (padded_batch(batch) - w.lane_tiles * 64) / 16;
     return launch(cmp ? gen_kernel<true> : gen_kernel<false>, ls.grid, ls.threads, kLdsBytes, st, a);
 }
 
@@ -810,22 +971,15 @@ static int eval_common(bool cmp, int mode, int party, int n, size_t batch, const
     a.y_share = d_y; a.tri_a = d_ta; a.tri_b = d_tb;
     a.batch = batch; a.n = n; a.party = party;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const bool quad = use_quad_layout(batch, dev);
-    const LaunchShape ls = shape_for(batch, dev, quad ? 16 : 64);
-    a.balance = ls.balance;
-    void (*kernel)(EvalArgs);
-    if (quad) {
-        kernel = !cmp ? (mode == kPlain ? eval_quad_kernel<false, kPlain> : eval_quad_kernel<false, kSign>)
-                      : mode == kPlain ? eval_quad_kernel<true, kPlain>
-                      : mode == kSign  ? eval_quad_kernel<true, kSign>
-                                       : eval_quad_kernel<true, kReluOpen>;
-    } else {
-        kernel = !cmp ? (mode == kPlain ? eval_kernel<false, kPlain> : eval_kernel<false, kSign>)
-                      : mode == kPlain ? eval_kernel<true, kPlain>
-                      : mode == kSign  ? eval_kernel<true, kSign>
-                                       : eval_kernel<true, kReluOpen>;
+    a.lane_tiles = 0; a.quad_tiles = 0;
+    if (use_quad_layout(batch, dev)) {
+        const LaunchShape ls = shape_for(batch, dev, 16);
+        return launch(pick_eval_quad_kernel(cmp, mode, ls.balance != 0), ls.grid, ls.threads, kLdsBytes, st, a);
     }
-    return launch(kernel, ls.grid, ls.threads, kLdsBytes, st, a);
+    const LaunchShape ls = shape_for(batch, dev);
+    const WorkSplit w = split_work(batch, ls);
+    a.lane_tiles = w.lane_tiles; a.quad_tiles = w.quad_tiles;
+    return launch(pick_eval_kernel(cmp, mode), ls.grid, ls.threads, kLdsBytes, st, a);
 }
 
 static unsigned elementwise_grid(size_t batch)

@@ -98,6 +98,24 @@ def test_both_layouts_around_the_switch(kind, n, offset):
     check_full(kind, n, w.gen, x)
 
 
+# From the switch on, full passes (one 64-element tile for every wavefront of the grid: twice
+# fss.quad_layout_below() elements) run one lane per element, and what is left after the last full
+# pass runs four lanes per element INSIDE THE SAME LAUNCH when it is shorter than the switch, one lane
+# per element otherwise.  Remainders of every kind, on both sides of that second switch.
+@pytest.mark.parametrize("kind", ["cmp", "eq"])
+@pytest.mark.parametrize("n,passes,rest", [(32, 1, 1), (32, 1, 15), (32, 1, 16), (32, 1, 17), (32, 1, 1000), (32, 1, 64 * 256),
+                                           (32, 1, -1), (32, 1, 0), (32, 1, 63), (12, 2, 777), (16, 1, 4097), (32, 3, 16384)])
+def test_remainder_after_full_passes(kind, n, passes, rest):
+    switch = fss.quad_layout_below()
+    full = 2 * switch                                   # elements of one full pass
+    batch = passes * full + (rest if rest > 0 else switch + rest)      # rest <= 0: around the second switch
+    w = W.uniform_workload(kind, n, batch, seed=9000 + 10 * n + passes + rest)
+    x = w.x.copy()
+    x[::5] = w.gen.alpha[::5]
+    x &= np.uint32(W.ring_mask(n))
+    check_full(kind, n, w.gen, x)
+
+
 def test_the_two_layouts_produce_the_same_bytes():
     """One set of per-element arguments placed in a batch below the switch and, repeated, in a batch
     above it: keys and shares of an element depend on that element's arguments only."""
