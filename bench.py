@@ -2,21 +2,28 @@
 """Benchmark of the FSS hot path on one MI355X.
 
 A step is one pass of the whole path over one synthetic batch: comparison KeyGen for B
-elements, then both parties' Eval.  The workload is the large-batch configuration
+elements, then both parties' Eval.  The headline workload is the large-batch configuration
 (B = 2^22, n = 32, uniform alpha and x), with every input and both key buffers resident in
 HBM before the timed region.  Prints ONE JSON line.
 
-  value      comparison evaluations per second per party = B / mean duration of one Eval launch
-  roofline   the dominant kernel (comparison Eval) against the LDS read peak that binds it,
-             with the vector-ALU and HBM fractions beside it
-  cpu_baseline  the plain-C oracle timed on this host's cores on a bounded sample
+  value        comparison evaluations per second per party = B / mean duration of one Eval launch
+  roofline     the dominant kernel (comparison Eval) against the LDS lookup rate that binds it
+               (algorithmic and issued lookups), with the vector-ALU and HBM fractions beside it;
+               roofline.gen: the same for the KeyGen kernel
+  configs      after the timed steps: each of the five benchmark configurations (and n = 16)
+               measured the same way -- Eval and KeyGen times (median, min), rates, fractions
+  sustained_clock_mhz   shader clock measured by a probe wavefront beside the Eval kernel
+  cpu_baseline the plain-C oracle timed on this host's cores on the first elements of the SAME
+               arrays the GPU step used, after the GPU's keys and shares for those elements have
+               been compared with the oracle's byte for byte
 
-Other lines on request: --batch N (small batches run the four-lanes-per-element kernels),
---workload eq (equality keys), --workload relu / maxpool (the paper's layers around the path).
+Other lines on request: --batch N, --workload eq / relu / maxpool / rounds / config (one
+configuration alone, the form the profiles under profiles/ are taken from).
 """
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -24,63 +31,313 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# ---- work model of the comparison Eval kernel ---------------------------------------------
-# (per evaluation at n = 32: 64 AES blocks of 160 four-byte table lookups each; the LDS read port,
-#  128 B/clk/CU, is the unit that binds; the vector ALU and HBM are reported beside it)
+# ---- work model -----------------------------------------------------------------------------
+# The AES of this path is table-driven out of LDS: 16 four-byte lookups per round and block, and
+# the LDS serves at most 32 such lookups per clock and CU (ds_read_b32; wider reads move more bytes
+# but fewer lookups, see the micro-benchmark).  That rate, as bytes, is the peak the kernels are
+# priced against; the vector ALU and HBM are reported beside it.
 N_BITS = 32
-AES_BLOCKS_PER_EVAL = 2 * N_BITS            # one child block + one sigma/tau block per level
-LOOKUPS_PER_BLOCK = 160                     # 16 table lookups x 10 rounds, 4 bytes each: what table-driven AES needs
-LDS_BYTES_PER_EVAL = AES_BLOCKS_PER_EVAL * LOOKUPS_PER_BLOCK * 4
-LDS_BYTES_ISSUED_PER_EVAL = 9282 * 4        # what the kernel issues (SQ_INSTS_LDS): coinciding lookups of the two
-                                            # blocks of a level are shared, unneeded final-round ones skipped
-VALU_OPS_PER_BLOCK = 257                    # vector-ALU instructions per AES block (SQ_INSTS_VALU, tree walk excluded)
-TREE_OPS_PER_LEVEL = 30                     # correction-word gating, selects, accumulate
-LANE_OPS_PER_EVAL = AES_BLOCKS_PER_EVAL * VALU_OPS_PER_BLOCK + N_BITS * TREE_OPS_PER_LEVEL
-HBM_BYTES_PER_EVAL = 804 + 4 + 4            # key planes read by Eval + x + out
-PEAK_LDS_GBS = 256 * 128 * 2.4              # 256 CUs x 128 B/clk x 2.4 GHz = 78,643 GB/s
+LOOKUPS_PER_BLOCK = 160                     # 16 table lookups x 10 rounds, 4 bytes each
+PEAK_LDS_GBS = 256 * 128 * 2.4              # 256 CUs x 32 lookups x 4 B per clock x 2.4 GHz = 78,643 GB/s
 PEAK_LANE_TOPS = 256 * 64 * 2.4e9 / 1e12    # 256 CUs x 64 lanes x 2.4 GHz = 39.3 T 32-bit lane-ops/s
 PEAK_HBM_GBS = 8000.0
-# HBM bytes per Eval launch at B = 2^22 from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by a plain
-# 1 GiB copy in the same run (profiles/cmp_2p22_hbm_counters.txt)
-MEASURED_HBM_BYTES_2P22 = (3_309_750 + 16_384) * 1024
 
 
-def cpu_baseline(sample: int):
-    """The oracle as it stands, on the host cores, on the first `sample` elements of the workload."""
+def aes_blocks(kind: str, op: str, n: int) -> int:
+    """AES blocks per element (Eval, per party) or per key pair (KeyGen), as the algorithms state them."""
+    return {("cmp", "eval"): 2 * n, ("eq", "eval"): n, ("cmp", "gen"): 6 * n, ("eq", "gen"): 4 * n}[(kind, op)]
+
+
+def hbm_bytes(kind: str, op: str, n: int) -> int:
+    """HBM bytes per element: Eval reads its key planes (all but the alpha share) and x, writes the
+    share; KeyGen reads alpha, r and two seeds and writes both keys."""
+    key = (40 + 24 * n) if kind == "cmp" else (32 + 16 * n)
+    return key - 4 + 4 + 4 if op == "eval" else 40 + 2 * key
+
+
+# Instructions the kernels actually issue, per launch, from rocprofv3 --pmc runs of
+# `bench.py --workload config --config <name>` (SQ_INSTS_LDS, SQ_INSTS_VALU: wavefront instructions,
+# 64 lanes each) and HBM traffic per launch (FETCH_SIZE + WRITE_SIZE scaled by a plain copy).
+# tests/test_profiles_match_bench.py checks every figure against the summaries under profiles/.
+ISSUED = {          # profiles/configs_sq_counters.txt
+    "config1": {"eval": {"lds": 2555904, "valu": 7179264}, "gen": {"lds": 7503872, "valu": 18807808}},
+    "config2": {"eval": {"lds": 83918848, "valu": 168050688}, "gen": {"lds": 311459840, "valu": 527695872}},
+    "config3": {"eval": {"lds": 116588544, "valu": 223313920}, "gen": {"lds": 343310336, "valu": 593693696}},
+    "config4": {"eval": {"lds": 29171712, "valu": 56300544}, "gen": {"lds": 85852160, "valu": 149083904}},
+    "config5": {"eval": {"lds": 608206848, "valu": 1151287296}, "gen": {"lds": 1791000576, "valu": 3062915072}},
+    "n16": {"eval": {"lds": 304119808, "valu": 577716224}, "gen": {"lds": 895516672, "valu": 1536188416}},
+}
+MEASURED_HBM_BYTES = {   # profiles/hbm_counters.txt
+    "config2": {"eval": 574736399, "gen": 1183091752},
+    "config3": {"eval": 656433435, "gen": 1330166602},
+    "config5": {"eval": 3405842163, "gen": 6946302624},
+}
+
+CONFIG_NAMES = ("config1", "config2", "config3", "config4", "config5", "n16")
+
+
+def median(v):
+    return statistics.median(v)
+
+
+def lds_gbs(kind, op, n, batch, ms):
+    return batch * aes_blocks(kind, op, n) * LOOKUPS_PER_BLOCK * 4 / (ms * 1e-3) / 1e9
+
+
+def fractions(name, kind, op, n, batch, ms):
+    """Roofline fractions of one launch of `ms` milliseconds."""
+    algo = lds_gbs(kind, op, n, batch, ms)
+    out = {"lds_algorithmic_gbs": algo, "lds_frac_algorithmic": algo / PEAK_LDS_GBS,
+           "hbm_gbs": batch * hbm_bytes(kind, op, n) / (ms * 1e-3) / 1e9}
+    out["hbm_frac"] = out["hbm_gbs"] / PEAK_HBM_GBS
+    issued = ISSUED.get(name, {}).get(op)
+    if issued:
+        out["lds_frac_issued"] = issued["lds"] * 64 * 4 / (ms * 1e-3) / 1e9 / PEAK_LDS_GBS
+        out["alu_frac"] = issued["valu"] * 64 / (ms * 1e-3) / 1e12 / PEAK_LANE_TOPS
+    return out
+
+
+class Device:
+    """Device buffers of one workload (inputs, both key buffers, both outputs)."""
+
+    def __init__(self, kind, n, w, dev):
+        import numpy as np
+        import torch
+        import paper_2006_04593_amd as fss
+        g = w.gen
+        self.kind, self.n, self.batch, self.w = kind, n, g.batch, w
+        self.alpha, self.r, self.x = (torch.from_numpy(a.view(np.int32)).to(dev) for a in (g.alpha, g.r, w.x))
+        self.s0, self.s1 = torch.from_numpy(g.seed0).to(dev), torch.from_numpy(g.seed1).to(dev)
+        nbytes = (fss.cmp_key_bytes if kind == "cmp" else fss.eq_key_bytes)(n, self.batch)
+        self.k = [torch.empty(nbytes, dtype=torch.uint8, device=dev) for _ in range(2)]
+        self.o = [torch.empty(self.batch, dtype=torch.int32, device=dev) for _ in range(2)]
+        self.gen_fn = fss.cmp_gen if kind == "cmp" else fss.eq_gen
+        self.eval_fn = fss.cmp_eval if kind == "cmp" else fss.eq_eval
+
+    def gen(self, stream):
+        self.gen_fn(self.n, self.batch, self.alpha, self.r, self.s0, self.s1, self.k[0], self.k[1], stream=stream)
+
+    def eval(self, party, stream, x=None):
+        self.eval_fn(party, self.n, self.batch, self.k[party], self.x if x is None else x, self.o[party], stream=stream)
+
+    def step(self, stream, marks=None):
+        """KeyGen, Eval of party 0, Eval of party 1; with `marks`, HIP events around each call."""
+        import torch
+        if marks is None:
+            self.gen(stream); self.eval(0, stream); self.eval(1, stream)
+            return
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        e[0].record(stream); self.gen(stream)
+        e[1].record(stream); self.eval(0, stream)
+        e[2].record(stream); self.eval(1, stream)
+        e[3].record(stream)
+        marks.append(e)
+
+    def check_reconstruction(self):
+        import numpy as np
+        rec = (self.o[0] + self.o[1]).cpu().numpy().view(np.uint32)
+        g, x = self.w.gen, self.w.x
+        truth = (x <= g.alpha) if self.kind == "cmp" else (x == g.alpha)
+        mask = np.uint32(0xFFFFFFFF if self.n == 32 else (1 << self.n) - 1)
+        assert np.array_equal(rec & mask, truth.astype(np.uint32)), "reconstruction failed"
+
+
+def kernel_names(kind, batch):
+    import paper_2006_04593_amd as fss
+    quad = batch < fss.quad_layout_below()
+    return (f"{'eval_quad_kernel' if quad else 'eval_kernel'}<{kind}>", f"{'gen_quad_kernel' if quad else 'gen_kernel'}<{kind}>",
+            "four lanes per element" if quad else "one lane per element (a short rest four lanes per element)")
+
+
+def split_marks(marks):
+    gen_ms = [e[0].elapsed_time(e[1]) for e in marks]
+    ev_ms = [e[1].elapsed_time(e[2]) for e in marks] + [e[2].elapsed_time(e[3]) for e in marks]
+    return gen_ms, ev_ms
+
+
+def entry(name, kind, n, batch, gen_ms, ev_ms, what):
+    ek, gk, layout = kernel_names(kind, batch)
+    em, gm = median(ev_ms), median(gen_ms)
+    return {"name": name, "workload": what, "kind": kind, "n": n, "batch": batch, "register_layout": layout,
+            "eval_kernel": ek, "gen_kernel": gk, "eval_launches_timed": len(ev_ms), "gen_launches_timed": len(gen_ms),
+            "eval_ms_median": em, "eval_ms_min": min(ev_ms), "gen_ms_median": gm, "gen_ms_min": min(gen_ms),
+            "evals_per_s_per_party": batch / (em * 1e-3), "gen_key_pairs_per_s": batch / (gm * 1e-3),
+            "eval": fractions(name, kind, "eval", n, batch, em), "gen": fractions(name, kind, "gen", n, batch, gm)}
+
+
+def config_workload(name):
+    """(kind, n, workload, description) of a named configuration; config4 is handled by bench_rounds."""
+    from paper_2006_04593_amd import workloads as W
+    if name == "config1":
+        return "cmp", 32, W.config_workload(1), "cmp Gen + both Evals, 16,384 elements, uniform alpha and x"
+    if name == "config2":
+        return "eq", 32, W.config_workload(2), "eq Gen + both Evals, 2^20 elements, x = alpha on a seeded tenth"
+    if name == "config3":
+        return "cmp", 32, W.config_workload(3), "ReLU-layer comparison batch, 64x112x112 = 802,816 masked fixed-point activations"
+    if name == "config5":
+        return "cmp", 32, W.config_workload(5), "cmp Gen + both Evals, 2^22 elements, uniform alpha and x"
+    if name == "n16":
+        return "cmp", 16, W.uniform_workload("cmp", 16, 1 << 22, seed=W.BASE_SEED + 16), "cmp Gen + both Evals on the ring Z_2^16, 2^22 elements"
+    raise ValueError(name)
+
+
+def bench_pair(name, dev, reps, warm):
+    """One configuration of the form KeyGen + both parties' Eval."""
+    import torch
+    kind, n, w, what = config_workload(name)
+    d = Device(kind, n, w, dev)
+    stream = torch.cuda.current_stream()
+    for _ in range(warm):
+        d.step(stream)
+    torch.cuda.synchronize()
+    marks = []
+    for _ in range(reps):
+        d.step(stream, marks)
+    torch.cuda.synchronize()
+    d.check_reconstruction()
+    gen_ms, ev_ms = split_marks(marks)
+    return entry(name, kind, n, d.batch, gen_ms, ev_ms, what)
+
+
+def bench_rounds(dev, reps, warm):
+    """Configuration 4: a 3x3 stride-2 pad-1 max-pool of 64 x 112 x 112 activations as a running
+    maximum, eight DEPENDENT comparison rounds of 200,704 elements (round k compares the running
+    maximum with tap k under fresh keys).  The reveal and the update between rounds are done in the
+    clear by a few torch ops: they stand in for the protocol's messages and are not part of the method."""
+    import numpy as np
+    import torch
+    import paper_2006_04593_amd as fss
+    from paper_2006_04593_amd import workloads as W
+
+    n = N_BITS
+    taps = W.maxpool_taps(W.BASE_SEED + 4)                       # [9, B] int64
+    B = taps.shape[1]
+    T = lambda a: torch.from_numpy(a.view(np.int32) if a.dtype == np.uint32 else a).to(dev)
+    d_taps = [T((taps[k] & 0xFFFFFFFF).astype(np.uint32)) for k in range(9)]
+    stream = torch.cuda.current_stream()
+    keys, d_alpha, gen_ms = [], [], []
+    for rnd in range(1, W.MAXPOOL_ROUNDS + 1):
+        g = W.maxpool_round_keys(W.BASE_SEED + 4, rnd, B)
+        kk = [torch.empty(fss.cmp_key_bytes(n, B), dtype=torch.uint8, device=dev) for _ in range(2)]
+        args = [T(v) for v in (g.alpha, g.r, g.seed0, g.seed1)]
+        for rep in range(warm + max(reps // 4, 2)):                   # KeyGen of the round's 200,704 key pairs
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            fss.cmp_gen(n, B, *args, kk[0], kk[1], stream=stream)
+            e1.record(stream)
+            if rep >= warm:
+                gen_ms.append((e0, e1))
+        keys.append(kk)
+        d_alpha.append(args[0])
+    torch.cuda.synchronize()
+    gen_ms = [a.elapsed_time(b) for a, b in gen_ms]
+    o = [torch.empty(B, dtype=torch.int32, device=dev) for _ in range(2)]
+    marks = []
+
+    def step(timed):
+        m = d_taps[0].clone()
+        for k in range(1, 9):
+            x = m - d_taps[k] + d_alpha[k - 1]                  # the value both parties would reveal: (m - w_k) + alpha_k
+            for j in (0, 1):
+                if timed:
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                fss.cmp_eval(j, n, B, keys[k - 1][j], x, o[j], stream=stream)
+                if timed:
+                    e1.record(stream)
+                    marks.append((e0, e1))
+            m = torch.where((o[0] + o[1]) == 1, d_taps[k], m)   # 1{m - w_k <= 0}: the tap is at least the running maximum
+        return m
+
+    for _ in range(warm):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        m = step(True)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    agree = (m.cpu().numpy().astype(np.int64) == taps.max(axis=0)).mean()
+    assert agree > 0.9999, f"running maximum agrees with the plain max-pool on {agree} of the outputs"
+    ev_ms = [a.elapsed_time(b) for a, b in marks]
+    out = entry("config4", "cmp", n, B, gen_ms, ev_ms,
+                "running-maximum max-pool 3x3/2 of 64x112x112: 8 dependent rounds x both parties' Eval of 200,704 elements, fresh keys per round")
+    out.update({"rounds": 8, "eval_ms_sum_of_16": median(ev_ms) * 16, "step_ms_with_glue_in_the_clear": wall * 1e3 / reps,
+                "agreement_with_plain_maxpool": agree})
+    return out
+
+
+def bench_named(name, dev, reps, warm):
+    return bench_rounds(dev, reps, warm) if name == "config4" else bench_pair(name, dev, reps, warm)
+
+
+def sustained_clock_mhz(d, dev):
+    """Shader clock while the comparison Eval kernel runs: a one-wavefront probe on a second stream
+    (it sleeps, so it takes nothing from the kernel) spans a few Eval launches."""
+    import torch
+    import paper_2006_04593_amd as fss
+    khz = fss.wall_clock_khz()
+    if khz <= 0:
+        return None
+    ticks = torch.zeros(2, dtype=torch.int64, device=dev)
+    side = torch.cuda.Stream()
+    stream = torch.cuda.current_stream()
+    torch.cuda.synchronize()
+    d.eval(0, stream)                                            # the chip is under load when the probe starts
+    fss.clock_probe(ticks, 1200, stream=side)                    # about 4 ms
+    for _ in range(3):
+        d.eval(0, stream); d.eval(1, stream)
+    torch.cuda.synchronize()
+    c, wticks = (int(v) for v in ticks.cpu())
+    return c / wticks * khz / 1e3 if wticks > 0 else None
+
+
+def cpu_baseline(d, sample):
+    """The oracle as it stands, on the host cores, on the first `sample` elements of the very arrays
+    the GPU step used -- after the GPU's key planes and both parties' shares for those elements have
+    been compared with the oracle's."""
     import numpy as np
     import oracle
-    from paper_2006_04593_amd import workloads as W
     threads = oracle.set_threads(0)
-    w = W.uniform_workload("cmp", N_BITS, sample, seed=W.BASE_SEED + 5)
-    g = w.gen
+    g, x, n, kind = d.w.gen, d.w.x, d.n, d.kind
+    sample = min(sample, d.batch)
+    a, r, s0, s1, xs = g.alpha[:sample], g.r[:sample], g.seed0[:sample], g.seed1[:sample], x[:sample]
     t0 = time.perf_counter()
-    k0, k1 = oracle.gen("cmp", N_BITS, g.alpha, g.r, g.seed0, g.seed1)
+    ok = oracle.gen(kind, n, a, r, s0, s1)
     t1 = time.perf_counter()
-    o0 = oracle.eval_("cmp", 0, N_BITS, k0, w.x)
+    oo = [None, None]
+    oo[0] = oracle.eval_(kind, 0, n, ok[0], xs)
     t2 = time.perf_counter()
-    o1 = oracle.eval_("cmp", 1, N_BITS, k1, w.x)
+    oo[1] = oracle.eval_(kind, 1, n, ok[1], xs)
     t3 = time.perf_counter()
-    assert np.array_equal(o0 + o1, (w.x <= g.alpha).astype(np.uint32))
+    # parity of the GPU step with the oracle on those elements: every plane of both keys, both shares
+    for j in (0, 1):
+        mine = oracle.split_key(kind, n, d.batch, d.k[j].cpu().numpy())
+        ref = oracle.split_key(kind, n, sample, ok[j])
+        for plane, v in ref.items():
+            if plane == "bp":
+                continue
+            got = mine[plane][:, :sample] if plane in ("s_cw", "sigma_cw", "leaf") else mine[plane][:sample]
+            want = v[:, :sample] if plane in ("s_cw", "sigma_cw", "leaf") else v[:sample]
+            assert np.array_equal(got, want), f"GPU key {j} differs from the oracle's in plane {plane}"
+        assert np.array_equal(d.o[j].cpu().numpy().view(np.uint32)[:sample], oo[j]), f"GPU share {j} differs from the oracle's"
+        del mine
     per_party = ((t2 - t1) + (t3 - t2)) / 2
-    # the same code on one thread, on a sixteenth of the sample
-    small = max(sample // 16, 1)
+    small = max(sample // 16, 1)                                 # the same code on one thread, on a sixteenth of the sample
     oracle.set_threads(1)
     t4 = time.perf_counter()
-    k0s, _ = oracle.gen("cmp", N_BITS, g.alpha[:small], g.r[:small], g.seed0[:small], g.seed1[:small])
+    ks, _ = oracle.gen(kind, n, a[:small], r[:small], s0[:small], s1[:small])
     t5 = time.perf_counter()
-    oracle.eval_("cmp", 0, N_BITS, k0s, w.x[:small])
+    oracle.eval_(kind, 0, n, ks, xs[:small])
     t6 = time.perf_counter()
     oracle.set_threads(0)
     return {
-        "value": sample / per_party,
-        "unit": "evals/s/party",
-        "cores": threads,
-        "kind": "oracle",
-        "sample": f"first-seed {sample} elements of the same workload: cmp Gen {t1 - t0:.2f} s, "
+        "value": sample / per_party, "unit": "evals/s/party", "cores": threads, "kind": "oracle",
+        "sample": f"the first {sample} of the {d.batch} elements the GPU step ran on (same alpha, r, seeds, x): Gen {t1 - t0:.2f} s, "
                   f"Eval party0 {t2 - t1:.2f} s, party1 {t3 - t2:.2f} s",
+        "parity": f"GPU keys (every plane, both parties) and both parties' shares equal the oracle's on those {sample} elements",
         "gen_pairs_per_s": sample / (t1 - t0),
-        "one_thread_evals_per_s": small / (t6 - t5),
-        "one_thread_gen_pairs_per_s": small / (t5 - t4),
+        "one_thread_evals_per_s": small / (t6 - t5), "one_thread_gen_pairs_per_s": small / (t5 - t4),
     }
 
 
@@ -137,8 +394,8 @@ def relu_layer_bench(args, dev):
     x = (masked[0] + masked[1]).cpu().numpy().view(np.uint32)
     le = (x <= g.alpha)
     assert np.array_equal(rec, np.where(le, 0, y & 0xFFFFFFFF).astype(np.uint32)), "ReLU reconstruction failed"
-    ms = sum(a.elapsed_time(b) for a, b in open_ms) / len(open_ms)
-    lds_gbs = B * LDS_BYTES_PER_EVAL / (ms * 1e-3) / 1e9
+    ms = median([a.elapsed_time(b) for a, b in open_ms])
+    gbs = lds_gbs("cmp", "eval", n, B, ms)
     return {
         "metric": "shared ReLU elements/sec per party (n=32, lambda=128)",
         "value": B / (ms * 1e-3), "unit": "elements/s/party", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -147,8 +404,8 @@ def relu_layer_bench(args, dev):
         "config": {"workload": "ReLU layer 64x112x112 = 802816 fixed-point activations: Sign mask + fused comparison/open "
                                "round + finish, both parties", "batch": B, "n": n, "lambda": 128},
         "relu_open_ms": ms,
-        "roofline": {"bound": "lds", "kernel": "eval_kernel<cmp, relu-open>", "achieved": lds_gbs, "peak": PEAK_LDS_GBS,
-                     "unit": "GB/s", "frac": lds_gbs / PEAK_LDS_GBS, "traffic": None},
+        "roofline": {"bound": "lds", "kernel": "eval_kernel<cmp, relu-open>", "achieved": gbs, "peak": PEAK_LDS_GBS,
+                     "unit": "GB/s", "frac": gbs / PEAK_LDS_GBS, "traffic": None},
     }
 
 
@@ -228,9 +485,9 @@ def maxpool_layer_bench(args, dev):
     win = np.lib.stride_tricks.sliding_window_view(x, (k, k), axis=(1, 2))[:, ::2, ::2].reshape(rows, m)
     agree = (y == (win.max(axis=1) & 0xFFFFFFFF).astype(np.uint32)).mean()
     assert agree > 0.99, f"max-pool agreement {agree}"       # ties and Sign wrap-arounds aside
-    cmp_ms = sum(e[0].elapsed_time(e[1]) for e in marks) / len(marks)
-    eq_ms = sum(e[2].elapsed_time(e[3]) for e in marks) / len(marks)
-    lds_gbs = ncmp * LDS_BYTES_PER_EVAL / (cmp_ms * 1e-3) / 1e9
+    cmp_ms = median([e[0].elapsed_time(e[1]) for e in marks])
+    eq_ms = median([e[2].elapsed_time(e[3]) for e in marks])
+    gbs = lds_gbs("cmp", "eval", n, ncmp, cmp_ms)
     return {
         "metric": "shared MaxPool windows/sec per party (3x3 stride 2, n=32, lambda=128)",
         "value": rows / ((wall / args.steps) / 2), "unit": "windows/s/party", "n_gpus": 1, "steps": args.steps,
@@ -240,83 +497,64 @@ def maxpool_layer_bench(args, dev):
                                f"{rows} windows, {ncmp} comparisons + {neq} equalities + {neq} products per party",
                    "n": n, "lambda": 128},
         "cmp_eval_ms": cmp_ms, "cmp_evals_per_s": ncmp / (cmp_ms * 1e-3), "eq_eval_ms": eq_ms,
-        "eq_evals_per_s": neq / (eq_ms * 1e-3), "agreement_with_plain_maxpool": agree,
-        "roofline": {"bound": "lds", "kernel": "eval_kernel<cmp, sign>", "achieved": lds_gbs, "peak": PEAK_LDS_GBS,
-                     "unit": "GB/s", "frac": lds_gbs / PEAK_LDS_GBS, "traffic": None},
+        "eq_evals_per_s": neq / (eq_ms * 1e-3), "eq_lds_frac_algorithmic": lds_gbs("eq", "eval", n, neq, eq_ms) / PEAK_LDS_GBS,
+        "agreement_with_plain_maxpool": agree,
+        "roofline": {"bound": "lds", "kernel": "eval_kernel<cmp, sign>", "achieved": gbs, "peak": PEAK_LDS_GBS,
+                     "unit": "GB/s", "frac": gbs / PEAK_LDS_GBS, "traffic": None},
     }
 
 
-def dependent_rounds_bench(args, dev):
-    """Benchmark configuration 4: a 3x3 stride-2 pad-1 max-pool of 64 x 112 x 112 activations as a running
-    maximum, eight DEPENDENT comparison rounds of 200,704 elements (round k compares the running
-    maximum with tap k under fresh keys).  The reveal and the update between rounds are done in the
-    clear by a few torch ops: they stand in for the protocol's messages and are not part of the method."""
+def streamed_bench(args, dev):
+    """Keys in pinned host memory, imported chunk by chunk during evaluation (fss_cmp_eval_streamed)."""
     import numpy as np
     import torch
-
     import paper_2006_04593_amd as fss
     from paper_2006_04593_amd import workloads as W
 
-    n = N_BITS
-    taps = W.maxpool_taps(W.BASE_SEED + 4)                       # [9, B] int64
-    B = taps.shape[1]
-
-    def T(a):
-        return torch.from_numpy(a.view(np.int32) if a.dtype == np.uint32 else a).to(dev)
-
-    d_taps = [T((taps[k] & 0xFFFFFFFF).astype(np.uint32)) for k in range(9)]
-    keys, d_alpha = [], []
-    for rnd in range(1, W.MAXPOOL_ROUNDS + 1):
-        g = W.maxpool_round_keys(W.BASE_SEED + 4, rnd, B)
-        kk = [torch.empty(fss.cmp_key_bytes(n, B), dtype=torch.uint8, device=dev) for _ in range(2)]
-        fss.cmp_gen(n, B, T(g.alpha), T(g.r), T(g.seed0), T(g.seed1), kk[0], kk[1])
-        keys.append(kk)
-        d_alpha.append(T(g.alpha))
-    torch.cuda.synchronize()
-    o = [torch.empty(B, dtype=torch.int32, device=dev) for _ in range(2)]
+    n, B, chunk = N_BITS, args.batch, 1 << 18
+    w = W.uniform_workload("cmp", n, B, seed=W.BASE_SEED + 5)
+    d = Device("cmp", n, w, dev)
     stream = torch.cuda.current_stream()
-    marks = []
-
-    def step(timed):
-        m = d_taps[0].clone()
-        for k in range(1, 9):
-            x = m - d_taps[k] + d_alpha[k - 1]                  # the value both parties would reveal: (m - w_k) + alpha_k
-            for j in (0, 1):
-                if timed:
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record(stream)
-                fss.cmp_eval(j, n, B, keys[k - 1][j], x, o[j], stream=stream)
-                if timed:
-                    e1.record(stream)
-                    marks.append((e0, e1))
-            m = torch.where((o[0] + o[1]) == 1, d_taps[k], m)   # 1{m - w_k <= 0}: the tap is at least the running maximum
-        return m
-
-    for _ in range(args.warmup):
-        step(False)
+    total = fss.cmp_chunked_key_bytes(n, B, chunk)
+    host = torch.empty(total, dtype=torch.uint8, pin_memory=True)
+    off = 0
+    T = lambda a: torch.from_numpy(a.view(np.int32) if a.dtype == np.uint32 else a).to(dev)
+    for first in range(0, B, chunk):
+        sl = slice(first, min(first + chunk, B))
+        ln = sl.stop - sl.start
+        nb = fss.cmp_key_bytes(n, ln)
+        kk = [torch.empty(nb, dtype=torch.uint8, device=dev) for _ in range(2)]
+        fss.cmp_gen(n, ln, T(w.gen.alpha[sl]), T(w.gen.r[sl]), T(w.gen.seed0[sl]), T(w.gen.seed1[sl]), kk[0], kk[1])
+        torch.cuda.synchronize()
+        host[off:off + nb].copy_(kk[0])
+        off += nb
+    staging = torch.empty(2 * fss.cmp_key_bytes(n, chunk), dtype=torch.uint8, device=dev)
+    side = torch.cuda.Stream()
+    ms = []
+    for rep in range(args.warmup + args.steps):
+        t0 = time.perf_counter()
+        fss.cmp_eval_streamed(0, n, B, chunk, host, d.x, d.o[0], staging, side, stream=stream)      # blocks until done
+        if rep >= args.warmup:
+            ms.append((time.perf_counter() - t0) * 1e3)
+    d.gen(stream); d.eval(0, stream)
+    ref = d.o[0].clone()
+    fss.cmp_eval_streamed(0, n, B, chunk, host, d.x, d.o[0], staging, side, stream=stream)
+    assert torch.equal(ref, d.o[0]), "streamed evaluation differs from the resident one"
+    t = median(ms)
+    dst = torch.empty(total, dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        m = step(True)
+    dst.copy_(host, non_blocking=True)
     torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    got = m.cpu().numpy().astype(np.int64)
-    agree = (got == taps.max(axis=0)).mean()
-    assert agree > 0.9999, f"running maximum agrees with the plain max-pool on {agree} of the outputs"
-    ms = [a.elapsed_time(b) for a, b in marks]
-    eval_ms = sum(ms) / len(ms)
-    lds_gbs = B * LDS_BYTES_PER_EVAL / (eval_ms * 1e-3) / 1e9
-    return {
-        "metric": "FSS comparison evals/sec per party in dependent rounds (n=32, lambda=128)",
-        "value": B / (eval_ms * 1e-3), "unit": "evals/s/party", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u32", "data": "synthetic",
-        "config": {"workload": f"running-maximum max-pool 3x3/2 of 64x112x112: 8 dependent rounds x both parties' Eval of {B} elements",
-                   "batch": B, "rounds": 8, "n": n, "lambda": 128},
-        "eval_ms": eval_ms, "eval_ms_sum_of_16": eval_ms * 16, "agreement_with_plain_maxpool": agree,
-        "roofline": {"bound": "lds", "kernel": "eval_kernel<cmp>", "achieved": lds_gbs, "peak": PEAK_LDS_GBS,
-                     "unit": "GB/s", "frac": lds_gbs / PEAK_LDS_GBS, "traffic": None},
-    }
+    copy_ms = (time.perf_counter() - t0) * 1e3
+    return {"metric": "FSS comparison evals/sec per party with keys streamed from host memory (n=32, lambda=128)",
+            "value": B / (t * 1e-3), "unit": "evals/s/party", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": t, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32", "data": "synthetic",
+            "config": {"workload": f"cmp Eval of {B} elements, keys in pinned host memory in chunks of {chunk}", "batch": B, "n": n},
+            "host_link_gbs": total / (t * 1e-3) / 1e9, "bare_copy_of_the_same_bytes_ms": copy_ms,
+            "bare_copy_gbs": total / (copy_ms * 1e-3) / 1e9,
+            "roofline": {"bound": "host link", "achieved": total / (t * 1e-3) / 1e9, "peak": total / (copy_ms * 1e-3) / 1e9,
+                         "unit": "GB/s", "frac": copy_ms / t, "traffic": None}}
 
 
 def main():
@@ -326,12 +564,15 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--batch", type=int, default=1 << 22, help="elements per step (default: the 2^22 configuration)")
     ap.add_argument("--cpu-sample", type=int, default=1 << 18, help="elements for the oracle timing; 0 skips it")
-    ap.add_argument("--workload", choices=["large", "eq", "relu", "maxpool", "rounds"], default="large",
-                    help="large: the headline 2^22 comparison Gen+Eval step; eq: the same step with the equality keys "
-                         "(Algorithms 1 and 2; --batch 1048576 is the 2^20 configuration); relu: one shared ReLU layer of "
-                         "64x112x112 activations (Sign mask, fused comparison+open round, finish) per party; "
-                         "maxpool: the paper's MaxPool (Algorithm 7), 3x3 stride 2 over 64x112x112; rounds: the same "
-                         "pooling as a running maximum, 8 dependent comparison rounds of 200,704 elements")
+    ap.add_argument("--workload", choices=["large", "eq", "relu", "maxpool", "rounds", "streamed", "config"], default="large",
+                    help="large: the headline 2^22 comparison Gen+Eval step, then every benchmark configuration; eq: the same step "
+                         "with the equality keys; relu: one shared ReLU layer of 64x112x112 activations; maxpool: the paper's "
+                         "MaxPool (Algorithm 7), 3x3 stride 2 over 64x112x112; rounds: configuration 4 alone; streamed: keys "
+                         "imported from pinned host memory; config: ONE configuration (--config) measured alone")
+    ap.add_argument("--config", choices=CONFIG_NAMES, default="config5", help="with --workload config")
+    ap.add_argument("--configs", default="all", help="with --workload large: 'all', 'none' or a comma list of configurations "
+                                                     "to measure after the timed steps")
+    ap.add_argument("--config-reps", type=int, default=10, help="timed repetitions of each configuration in the configs block")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also launch one plain elementwise copy over 1 GiB, so that a rocprofv3 --pmc run of this "
                          "command holds the counter's reading for a kernel of known traffic")
@@ -341,7 +582,6 @@ def main():
               "batch with no exchange); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
 
     import paper_2006_04593_amd as fss
@@ -350,87 +590,75 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    if args.workload == "relu":
-        print(json.dumps(relu_layer_bench(args, dev)))
-        return
-    if args.workload == "maxpool":
-        print(json.dumps(maxpool_layer_bench(args, dev)))
-        return
-    if args.workload == "rounds":
-        print(json.dumps(dependent_rounds_bench(args, dev)))
-        return
-    B, n = args.batch, N_BITS
-    cmp = args.workload != "eq"
-    if cmp:
-        w = W.uniform_workload("cmp", n, B, seed=W.BASE_SEED + 5, name="config5")
-    else:
-        w = W.equality_workload(n, B, seed=W.BASE_SEED + 2)           # x = alpha on a seeded tenth of the elements
-    g = w.gen
-    gen_fn, eval_fn, key_bytes_fn = (fss.cmp_gen, fss.cmp_eval, fss.cmp_key_bytes) if cmp else (fss.eq_gen, fss.eq_eval, fss.eq_key_bytes)
-    d_alpha, d_r, d_x = (torch.from_numpy(a.view(np.int32)).to(dev) for a in (g.alpha, g.r, w.x))
-    d_s0, d_s1 = torch.from_numpy(g.seed0).to(dev), torch.from_numpy(g.seed1).to(dev)
-    nbytes = key_bytes_fn(n, B)
-    k0 = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-    k1 = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-    o0 = torch.empty(B, dtype=torch.int32, device=dev)
-    o1 = torch.empty(B, dtype=torch.int32, device=dev)
-    stream = torch.cuda.current_stream()
-
-    def ev():
-        return torch.cuda.Event(enable_timing=True)
-
-    def step(marks=None):
-        if marks is not None:
-            e = [ev() for _ in range(4)]
-            e[0].record(stream)
-        gen_fn(n, B, d_alpha, d_r, d_s0, d_s1, k0, k1, stream=stream)
-        if marks is not None:
-            e[1].record(stream)
-        eval_fn(0, n, B, k0, d_x, o0, stream=stream)
-        if marks is not None:
-            e[2].record(stream)
-        eval_fn(1, n, B, k1, d_x, o1, stream=stream)
-        if marks is not None:
-            e[3].record(stream)
-            marks.append(e)
-
+    fss.prepare()
     if args.pmc_calibration:
         src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)      # 1 GiB read + 1 GiB written
         dst = torch.empty_like(src)
         torch.add(src, 1, out=dst)
         torch.cuda.synchronize()
         del src, dst
+    if args.workload == "relu":
+        print(json.dumps(relu_layer_bench(args, dev)))
+        return
+    if args.workload == "maxpool":
+        print(json.dumps(maxpool_layer_bench(args, dev)))
+        return
+    if args.workload == "streamed":
+        print(json.dumps(streamed_bench(args, dev)))
+        return
+    if args.workload == "rounds":
+        print(json.dumps(bench_rounds(dev, args.steps, args.warmup)))
+        return
+    if args.workload == "config":
+        print(json.dumps(bench_named(args.config, dev, args.steps, args.warmup)))
+        return
+
+    B, n = args.batch, N_BITS
+    cmp = args.workload != "eq"
+    kind = "cmp" if cmp else "eq"
+    name = "config5" if (cmp and B == 1 << 22) else ("config2" if (not cmp and B == 1 << 20) else f"{kind}-{B}")
+    if cmp:
+        w = W.uniform_workload("cmp", n, B, seed=W.BASE_SEED + 5, name="config5")
+    else:
+        w = W.equality_workload(n, B, seed=W.BASE_SEED + 2)           # x = alpha on a seeded tenth of the elements
+    d = Device(kind, n, w, dev)
+    stream = torch.cuda.current_stream()
 
     for _ in range(args.warmup):
-        step()
+        d.step(stream)
     torch.cuda.synchronize()
     marks = []
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step(marks)
+        d.step(stream, marks)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    d.check_reconstruction()                       # correctness of what was just timed, on every element
 
-    # correctness of what was just timed: reconstruction on every element
-    rec = (o0 + o1).cpu().numpy().view(np.uint32)
-    truth = (w.x <= g.alpha) if cmp else (w.x == g.alpha)
-    assert np.array_equal(rec, truth.astype(np.uint32)), "reconstruction failed"
-
-    gen_ms = [e[0].elapsed_time(e[1]) for e in marks]
-    ev_ms = [e[1].elapsed_time(e[2]) for e in marks] + [e[2].elapsed_time(e[3]) for e in marks]
-    eval_ms = sum(ev_ms) / len(ev_ms)
+    gen_ms, ev_ms = split_marks(marks)
+    eval_ms = sum(ev_ms) / len(ev_ms)              # mean over the timed region: what `value` is quoted on
     gen_mean = sum(gen_ms) / len(gen_ms)
-    evals_per_s = B / (eval_ms * 1e-3)
+    ek, gk, layout = kernel_names(kind, B)
+    fe, fg = fractions(name, kind, "eval", n, B, eval_ms), fractions(name, kind, "gen", n, B, gen_mean)
 
-    lane_layout = B >= fss.quad_layout_below()     # the instruction counts above belong to this layout
-    blocks = AES_BLOCKS_PER_EVAL if cmp else N_BITS                 # equality: one block per level
-    hbm_per_eval = HBM_BYTES_PER_EVAL if cmp else 540 + 4 + 4       # equality key planes read by Eval + x + out
-    lds_gbs = B * blocks * LOOKUPS_PER_BLOCK * 4 / (eval_ms * 1e-3) / 1e9
-    lane_tops = B * LANE_OPS_PER_EVAL / (eval_ms * 1e-3) / 1e12
-    hbm_gbs = B * hbm_per_eval / (eval_ms * 1e-3) / 1e9
+    def roofline(kernel, f, op, ms):
+        return {
+            "bound": "lds", "kernel": kernel, "achieved": f["lds_algorithmic_gbs"], "peak": PEAK_LDS_GBS, "unit": "GB/s",
+            "frac": f["lds_frac_algorithmic"],
+            "what": f"{aes_blocks(kind, op, n)} AES blocks x {LOOKUPS_PER_BLOCK} four-byte table lookups per element, over the mean launch "
+                    f"duration ({ms:.4f} ms, HIP events on the launch stream), against 32 lookups x 4 B per clock and CU at 2.4 GHz",
+            "frac_issued": f.get("lds_frac_issued"),
+            "traffic": MEASURED_HBM_BYTES.get(name, {}).get(op),
+            "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy)",
+            "traffic_algorithmic": B * hbm_bytes(kind, op, n),
+            "alu": {"frac": f.get("alu_frac"), "peak": PEAK_LANE_TOPS, "unit": "T 32-bit lane-ops/s"},
+            "hbm": {"achieved": f["hbm_gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": f["hbm_frac"],
+                    "bytes_per_element": hbm_bytes(kind, op, n)},
+        }
+
     out = {
         "metric": f"FSS {'comparison' if cmp else 'equality'} evals/sec per party (n=32, lambda=128)",
-        "value": evals_per_s,
+        "value": B / (eval_ms * 1e-3),
         "unit": "evals/s/party",
         "n_gpus": 1,
         "steps": args.steps,
@@ -441,37 +669,31 @@ def main():
         "vs_baseline": None,
         "dtype": "u32",
         "data": "synthetic",
-        "config": {"workload": f"{'large' if lane_layout else 'small'} batch: {'cmp' if cmp else 'eq'} Gen of {B} keys + both parties' Eval, n=32, "
-                               + ("uniform alpha and x" if cmp else "uniform alpha, x = alpha on a tenth of the elements") + ", SoA keys resident in HBM", "batch": B, "n": n, "lambda": 128,
-                   "register_layout": "one lane per element" if lane_layout else "four lanes per element"},
-        "eval_ms": eval_ms,
-        "eval_ms_min": min(ev_ms),
-        "gen_ms": gen_mean,
+        "config": {"workload": f"{'large' if B >= fss.quad_layout_below() else 'small'} batch: {kind} Gen of {B} keys + both parties' Eval, n=32, "
+                               + ("uniform alpha and x" if cmp else "uniform alpha, x = alpha on a tenth of the elements")
+                               + ", SoA keys resident in HBM", "batch": B, "n": n, "lambda": 128, "register_layout": layout},
+        "eval_ms": eval_ms, "eval_ms_median": median(ev_ms), "eval_ms_min": min(ev_ms),
+        "gen_ms": gen_mean, "gen_ms_median": median(gen_ms), "gen_ms_min": min(gen_ms),
         "gen_key_pairs_per_s": B / (gen_mean * 1e-3),
         "step_evals_per_s_incl_gen": 2 * B / (wall / args.steps),
-        # The AES of this path is table-driven out of LDS, and the LDS read port is the unit that
-        # binds: 160 four-byte lookups per AES block against 128 B/clk/CU.
-        "roofline": {
-            "bound": "lds",
-            "kernel": "eval_kernel<cmp>" if cmp else "eval_kernel<eq>",
-            "achieved": lds_gbs,
-            "peak": PEAK_LDS_GBS,
-            "unit": "GB/s",
-            "frac": lds_gbs / PEAK_LDS_GBS,
-            "traffic": MEASURED_HBM_BYTES_2P22 if (cmp and B == (1 << 22)) else None,
-            "traffic_unit": "HBM bytes per Eval launch (rocprofv3 FETCH_SIZE+WRITE_SIZE, scaled)",
-            "lds_issued_frac": B * LDS_BYTES_ISSUED_PER_EVAL / (eval_ms * 1e-3) / 1e9 / PEAK_LDS_GBS if (cmp and lane_layout) else None,
-            "alu": {"achieved": lane_tops, "peak": PEAK_LANE_TOPS, "unit": "T 32-bit lane-ops/s",
-                    "frac": lane_tops / PEAK_LANE_TOPS, "lane_ops_per_eval": LANE_OPS_PER_EVAL} if (cmp and lane_layout) else None,
-            "hbm": {"achieved": hbm_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": hbm_gbs / PEAK_HBM_GBS,
-                    "bytes_per_eval": hbm_per_eval},
-        },
+        "roofline": roofline(ek, fe, "eval", eval_ms),
     }
+    out["roofline"]["gen"] = roofline(gk, fg, "gen", gen_mean)
+    out["sustained_clock_mhz"] = sustained_clock_mhz(d, dev)
+    out["nominal_clock_mhz"] = 2400
     props = torch.cuda.get_device_properties(dev)
     out["device"] = {"name": props.name, "arch": getattr(props, "gcnArchName", None), "compute_units": props.multi_processor_count,
                      "lds_per_workgroup": getattr(props, "shared_memory_per_block", None)}
-    if args.cpu_sample > 0 and cmp:
-        out["cpu_baseline"] = cpu_baseline(args.cpu_sample)
+    if args.cpu_sample > 0:
+        out["cpu_baseline"] = cpu_baseline(d, args.cpu_sample)
+    del d
+    torch.cuda.empty_cache()
+    wanted = [] if args.configs == "none" else (list(CONFIG_NAMES) if args.configs == "all" else args.configs.split(","))
+    if cmp and B == 1 << 22 and wanted:
+        out["configs"] = []
+        for cname in wanted:
+            out["configs"].append(bench_named(cname, dev, args.config_reps, 2))
+            torch.cuda.empty_cache()
     print(json.dumps(out))
 
 

@@ -252,6 +252,15 @@ int fss_cmp_eval_streamed_static(int party, int n, size_t batch, size_t chunk, c
  * be queried. */
 size_t fss_quad_layout_below(void);
 
+/* Measurement aid (no part of the method): the clock the chip sustains.  fss_clock_probe enqueues
+ * ONE wavefront that sleeps for `iterations` (1 .. 2^20) x 8128 shader clocks -- about 3.4 us each --
+ * and then writes d_ticks[0] = shader clocks elapsed, d_ticks[1] = ticks of the constant-rate wall
+ * clock elapsed (two u64, device memory, 8-byte aligned).  Launched on a second stream beside the
+ * kernels of interest, shader clocks / wall ticks x fss_wall_clock_khz() is the clock in kHz under
+ * that load.  fss_wall_clock_khz: rate of the wall clock of the current device, 0 if unknown. */
+int fss_clock_probe(uint64_t *d_ticks, uint32_t iterations, fss_stream_t stream);
+int fss_wall_clock_khz(void);
+
 /* Text for a return code (static storage, never NULL). */
 const char *fss_strerror(int code);
 

@@ -14,11 +14,13 @@ from .binding import (  # noqa: F401
     mul_open,
     FssError,
     build,
+    clock_probe,
     cmp_chunked_key_bytes,
     cmp_eval,
     cmp_eval_streamed,
     cmp_eval_streamed_static,
     static_staging_bytes,
+    wall_clock_khz,
     cmp_gen,
     cmp_key_bytes,
     eq_eval,

@@ -17,7 +17,7 @@ EXPORTS = ("fss_cmp_key_bytes", "fss_eq_key_bytes", "fss_cmp_gen", "fss_cmp_eval
            "fss_sign_mask", "fss_sign_eval", "fss_relu_open", "fss_relu_finish", "fss_eq_mask", "fss_eq_masked_eval",
            "fss_argmax_diff_mask", "fss_argmax_count_mask", "fss_maxpool_unroll", "fss_mul_open", "fss_dot_finish",
            "fss_cmp_chunked_key_bytes",
-           "fss_cmp_eval_streamed", "fss_cmp_eval_streamed_static", "fss_static_staging_bytes", "fss_prepare", "fss_quad_layout_below", "fss_strerror", "fss_last_hip_error")
+           "fss_cmp_eval_streamed", "fss_cmp_eval_streamed_static", "fss_static_staging_bytes", "fss_prepare", "fss_clock_probe", "fss_wall_clock_khz", "fss_quad_layout_below", "fss_strerror", "fss_last_hip_error")
 
 HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -105,6 +105,10 @@ def lib() -> C.CDLL:
         L.fss_cmp_eval_streamed_static.restype = i
         L.fss_static_staging_bytes.argtypes = []
         L.fss_static_staging_bytes.restype = sz
+        L.fss_clock_probe.argtypes = [vp, C.c_uint32, vp]
+        L.fss_clock_probe.restype = i
+        L.fss_wall_clock_khz.argtypes = []
+        L.fss_wall_clock_khz.restype = i
         L.fss_prepare.argtypes = []
         L.fss_prepare.restype = i
         L.fss_quad_layout_below.argtypes = []
@@ -284,6 +288,15 @@ def dot_finish(party: int, n: int, rows: int, m: int, d_delta0, d_delta1, d_eps0
     _check(lib().fss_dot_finish(party, n, rows, m, _dev("delta0", d_delta0, w), _dev("delta1", d_delta1, w), _dev("eps0", d_eps0, w),
                                 _dev("eps1", d_eps1, w), _dev("tri_a", d_tri_a, w), _dev("tri_b", d_tri_b, w), _dev("tri_c", d_tri_c, w),
                                 _dev("out", d_out, 4 * rows), _stream(stream)))
+
+
+def clock_probe(d_ticks, iterations: int, stream=None) -> None:
+    """fss_clock_probe: d_ticks is a device tensor of two int64 (shader clocks, wall-clock ticks)."""
+    _check(lib().fss_clock_probe(_dev("ticks", d_ticks, 16), iterations, _stream(stream)))
+
+
+def wall_clock_khz() -> int:
+    return int(lib().fss_wall_clock_khz())
 
 
 def prepare() -> None:

@@ -146,7 +146,10 @@ __global__ __launch_bounds__(kThreads) void bitplane_engine(uint32_t *out, int i
 // REPL = true: the kernels' pattern ((entry << 8) | copy of lane); false: one 1-KiB table for all lanes.
 // The 16 addresses of a lane are drawn once; every iteration issues the 16 loads, waits, and
 // folds the results with 16 two-operand XORs.
-template <bool REPL>
+// FAIR: the wavefront lowers its priority as it advances (3, 2, 1, 0 from 0, 1/2, 3/4, 7/8 of its
+// iterations), as the FSS kernels do per tile; without it the SIMD serves its oldest wavefront first,
+// the old ones finish early and the launch ends with too few wavefronts to keep the LDS busy.
+template <bool REPL, bool FAIR>
 __global__ __launch_bounds__(kThreads) void lds_rate(uint32_t *out, int iters)
 {
     extern __shared__ uint32_t lds[];
@@ -161,7 +164,13 @@ __global__ __launch_bounds__(kThreads) void lds_rate(uint32_t *out, int iters)
         const uint32_t e = (r >> 13) & 255u;
         a[k] = REPL ? ((e << 8) | lane4 | ((k & 1) << 7) | ((k & 2) << 15)) : ((e << 2) | (k << 10));
     }
+    if (FAIR) __builtin_amdgcn_s_setprio(3);
     for (int it = 0; it < iters; it++) {
+        if (FAIR) {
+            if (it == (iters >> 1)) __builtin_amdgcn_s_setprio(2);
+            else if (it == iters - (iters >> 2)) __builtin_amdgcn_s_setprio(1);
+            else if (it == iters - (iters >> 3)) __builtin_amdgcn_s_setprio(0);
+        }
         uint32_t v[16];
 #pragma unroll
         for (int k = 0; k < 16; k++) asm volatile("ds_read_b32 %0, %1" : "=v"(v[k]) : "v"(a[k]) : "memory");
@@ -290,8 +299,9 @@ int main()
     uint32_t *out;
     CK(hipMalloc(&out, (size_t)cus * 8 * kThreads * 4));
     CK(hipFuncSetAttribute((const void *)lds_engine, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes));
-    CK(hipFuncSetAttribute((const void *)lds_rate<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes));
-    CK(hipFuncSetAttribute((const void *)lds_rate<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes));
+    CK(hipFuncSetAttribute((const void *)lds_rate<true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes));
+    CK(hipFuncSetAttribute((const void *)lds_rate<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes));
+    CK(hipFuncSetAttribute((const void *)lds_rate<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes));
     float ms;
     const double ghz = 2.4;
 
@@ -315,10 +325,13 @@ int main()
     {
         const int iters = 20000;
         const double lanes = (double)cus * kThreads * iters * 16;
-        if (time_launch([&] { hipLaunchKernelGGL(lds_rate<true>, dim3(cus), dim3(kThreads), kLdsBytes, 0, out, iters); }, &ms)) return 1;
+        if (time_launch([&] { hipLaunchKernelGGL((lds_rate<true, false>), dim3(cus), dim3(kThreads), kLdsBytes, 0, out, iters); }, &ms)) return 1;
         printf("  32 copies per entry (kernels' layout) %8.3f ms  %6.1f lookups/clk/CU  %6.1f TB/s\n", ms,
                lanes / (ms * 1e-3) / cus / (ghz * 1e9), lanes * 4 / (ms * 1e-3) / 1e12);
-        if (time_launch([&] { hipLaunchKernelGGL(lds_rate<false>, dim3(cus), dim3(kThreads), kLdsBytes, 0, out, iters); }, &ms)) return 1;
+        if (time_launch([&] { hipLaunchKernelGGL((lds_rate<true, true>), dim3(cus), dim3(kThreads), kLdsBytes, 0, out, iters); }, &ms)) return 1;
+        printf("  the same, priority falling with progress %5.3f ms  %6.1f lookups/clk/CU  %6.1f TB/s\n", ms,
+               lanes / (ms * 1e-3) / cus / (ghz * 1e9), lanes * 4 / (ms * 1e-3) / 1e12);
+        if (time_launch([&] { hipLaunchKernelGGL((lds_rate<false, false>), dim3(cus), dim3(kThreads), kLdsBytes, 0, out, iters); }, &ms)) return 1;
         printf("  one 1-KiB table, no replication       %8.3f ms  %6.1f lookups/clk/CU  %6.1f TB/s\n", ms,
                lanes / (ms * 1e-3) / cus / (ghz * 1e9), lanes * 4 / (ms * 1e-3) / 1e12);
     }

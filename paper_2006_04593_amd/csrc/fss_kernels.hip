@@ -456,6 +456,17 @@ __global__ void relu_finish_kernel(const uint32_t *d0, const uint32_t *d1, const
     }
 }
 
+// One wavefront that sleeps for `iterations` x 8128 shader clocks and reports how many shader clocks
+// and how many ticks of the constant-rate wall clock went by: their ratio is the clock the chip
+// sustains under whatever runs beside it.  (s_sleep keeps the wavefront off the execution units.)
+__global__ void clock_probe_kernel(unsigned long long *ticks, uint32_t iterations)
+{
+    const unsigned long long c0 = clock64(), w0 = wall_clock64();
+    for (uint32_t i = 0; i < iterations; i++) __builtin_amdgcn_s_sleep(127);
+    const unsigned long long c1 = clock64(), w1 = wall_clock64();
+    if (threadIdx.x == 0) { ticks[0] = c1 - c0; ticks[1] = w1 - w0; }
+}
+
 // ------------------------------------------------------------------------------------
 // KeyGen: Algorithm 1 (CMP = false) and Algorithm 3 (CMP = true), shortened correction words
 // ------------------------------------------------------------------------------------
@@ -1293,6 +1304,21 @@ int fss_cmp_eval_streamed_static(int party, int n, size_t batch, size_t chunk, c
     rc = prepare_static_staging(&st);       // after the first call on a device: a table lookup
     if (rc != FSS_OK) return rc;
     return streamed_walk(party, n, batch, chunk, h_key_chunks, d_x, d_out, st.ptr, st.ev, copy_stream, stream);
+}
+
+int fss_clock_probe(uint64_t *d_ticks, uint32_t iterations, fss_stream_t stream)
+{
+    using namespace fss;
+    if (!d_ticks || misaligned(d_ticks, 8) || iterations == 0 || iterations > (1u << 20)) return FSS_EINVAL;
+    return launch(clock_probe_kernel, 1, 64, 0, static_cast<hipStream_t>(stream), reinterpret_cast<unsigned long long *>(d_ticks), iterations);
+}
+
+int fss_wall_clock_khz(void)
+{
+    int dev = 0, khz = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess) return 0;
+    return khz;
 }
 
 int fss_prepare(void)
