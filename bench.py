@@ -73,7 +73,8 @@ MEASURED_HBM_BYTES = {   # profiles/hbm_counters.txt
     "config5": {"eval": 3405842163, "gen": 6946302624},
 }
 
-CONFIG_NAMES = ("config1", "config2", "config3", "config4", "config5", "n16")
+CONFIG_NAMES = ("config1", "config2", "config3", "config4", "config5", "n16")     # the `configs` block of the default run
+RING_NAMES = ("n8", "n16", "n24", "n28")                                            # smaller rings, each measurable alone
 
 
 def median(v):
@@ -176,8 +177,9 @@ def config_workload(name):
         return "cmp", 32, W.config_workload(3), "ReLU-layer comparison batch, 64x112x112 = 802,816 masked fixed-point activations"
     if name == "config5":
         return "cmp", 32, W.config_workload(5), "cmp Gen + both Evals, 2^22 elements, uniform alpha and x"
-    if name == "n16":
-        return "cmp", 16, W.uniform_workload("cmp", 16, 1 << 22, seed=W.BASE_SEED + 16), "cmp Gen + both Evals on the ring Z_2^16, 2^22 elements"
+    if name in RING_NAMES:
+        n = int(name[1:])
+        return "cmp", n, W.uniform_workload("cmp", n, 1 << 22, seed=W.BASE_SEED + n), f"cmp Gen + both Evals on the ring Z_2^{n}, 2^22 elements"
     raise ValueError(name)
 
 
@@ -569,7 +571,7 @@ def main():
                          "with the equality keys; relu: one shared ReLU layer of 64x112x112 activations; maxpool: the paper's "
                          "MaxPool (Algorithm 7), 3x3 stride 2 over 64x112x112; rounds: configuration 4 alone; streamed: keys "
                          "imported from pinned host memory; config: ONE configuration (--config) measured alone")
-    ap.add_argument("--config", choices=CONFIG_NAMES, default="config5", help="with --workload config")
+    ap.add_argument("--config", choices=sorted(set(CONFIG_NAMES + RING_NAMES)), default="config5", help="with --workload config")
     ap.add_argument("--configs", default="all", help="with --workload large: 'all', 'none' or a comma list of configurations "
                                                      "to measure after the timed steps")
     ap.add_argument("--config-reps", type=int, default=10, help="timed repetitions of each configuration in the configs block")
