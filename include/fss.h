@@ -243,13 +243,19 @@ int fss_cmp_eval_streamed_static(int party, int n, size_t batch, size_t chunk, c
                                  const uint32_t *d_x, uint32_t *d_out, fss_stream_t copy_stream,
                                  fss_stream_t stream);
 
-/* Register layouts.  The KeyGen and Eval kernels exist in two layouts with identical results
- * (keys and shares agree byte for byte): one lane per element (highest throughput) and four
+/* Register layouts.  The KeyGen and Eval kernels walk an element in one of two layouts with identical
+ * results (keys and shares agree byte for byte): one lane per element (highest throughput) and four
  * lanes per element (a quarter of the dependent work per wavefront and four times the wavefronts:
- * lower latency while a batch is too small to fill the device).  The entry points pick by batch
- * size.  fss_quad_layout_below() returns the batch size below which the current device uses the
- * four-lane layout (device-dependent: 512 elements per compute unit), or 0 if the device cannot
- * be queried. */
+ * lower latency while there is too little work to fill the device).  The entry points pick by batch
+ * size: below fss_quad_layout_below() elements (512 per compute unit) everything runs four lanes per
+ * element; from there on, one lane per element in rows of 64 elements per compute unit (16 rows =
+ * 2 * fss_quad_layout_below() elements make a full pass), and what is left after the last full pass
+ * -- if it is shorter than fss_quad_layout_below() -- as well as the last partial row run four lanes
+ * per element inside the same launch.  fss_quad_layout_below() returns that size for the current
+ * device, or 0 if the device cannot be queried.
+ * The kernels change the priority of their own wavefronts (s_setprio) while they run, so that the
+ * wavefronts sharing a SIMD advance together; kernels of other streams running beside them on the
+ * same compute units compete with priorities between 0 and 3. */
 size_t fss_quad_layout_below(void);
 
 /* Measurement aid (no part of the method): the clock the chip sustains.  fss_clock_probe enqueues

@@ -128,6 +128,26 @@ def test_streamed_evaluation_arguments(lib):
     assert lib.fss_cmp_eval_streamed(0, 32, 0, 64, None, None, None, None, S1, S2) == 0
 
 
+def test_static_staging_arguments(lib):
+    A, S1, S2 = 0x10000, 0x1000, 0x2000
+    assert lib.fss_static_staging_bytes() == 32 << 20
+    assert lib.fss_cmp_eval_streamed_static(0, 32, 100, 100, A, A, A, S1, S2) == -1       # chunk not a multiple of 64
+    assert lib.fss_cmp_eval_streamed_static(0, 32, 100, 64, A, A, A, S1, S1) == -1        # one stream for both roles
+    assert lib.fss_cmp_eval_streamed_static(2, 32, 100, 64, A, A, A, S1, S2) == -1
+    assert lib.fss_cmp_eval_streamed_static(0, 32, 100, 20736 + 64, A, A, A, S1, S2) == -4   # beyond the built-in staging memory
+    assert lib.fss_cmp_eval_streamed_static(0, 8, 100, 20736 + 64, None, A, A, S1, S2) == -1  # fits at n = 8; NULL keys
+    assert lib.fss_cmp_eval_streamed_static(0, 32, 0, 64, None, None, None, S1, S2) == 0
+    assert b"limit" in lib.fss_strerror(-4)
+
+
+def test_clock_probe_arguments(lib):
+    A = 0x10000
+    assert lib.fss_clock_probe(None, 10, None) == -1
+    assert lib.fss_clock_probe(A + 4, 10, None) == -1          # two u64: 8-byte alignment
+    assert lib.fss_clock_probe(A, 0, None) == -1
+    assert lib.fss_clock_probe(A, (1 << 20) + 1, None) == -1    # bounded: the probe always ends
+
+
 def test_layout_switch_query(lib):
     # 512 elements per compute unit on a device; 0 where there is none to ask
     assert lib.fss_quad_layout_below() % 512 == 0

@@ -248,6 +248,16 @@ def test_empty_batch_is_a_noop_and_errors_raise():
     torch.cuda.synchronize()
 
 
+def test_clock_probe_reads_a_plausible_clock():
+    ticks = torch.zeros(2, dtype=torch.int64, device=dev())
+    fss.clock_probe(ticks, 100)
+    torch.cuda.synchronize()
+    shader, wall = (int(v) for v in ticks.cpu())
+    khz = fss.wall_clock_khz()
+    assert khz > 0 and wall > 0 and shader >= 100 * 64 * 127
+    assert 500 < shader / wall * khz / 1e3 < 3500          # MHz
+
+
 def test_binding_rejects_buffers_that_are_too_short_or_not_on_the_gpu():
     n, batch = 32, 1000
     i32 = lambda count: torch.zeros(count, dtype=torch.int32, device=dev())
