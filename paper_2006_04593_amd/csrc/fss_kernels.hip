@@ -305,26 +305,13 @@ __global__ __launch_bounds__(kThreads) void eval_kernel(EvalArgs a)
     const size_t stride = (size_t)(blockDim.x >> 6) * gridDim.x;
     const size_t slot = (size_t)wave_index() * gridDim.x + blockIdx.x;
 
-    // the first tile's inputs are requested before the tables are filled
-    size_t tile = slot;
-    size_t e = tile * 64 + lane;
-    bool live = tile < a.lane_tiles && e < a.batch;
-    LaneInputs<CMP> in = {};
-    if (live) in = load_lane_inputs<CMP, MODE>(a, p, e);
-
     fill_tables(lds);
     __syncthreads();
     const LaneBase L = lane_base(lds);
 
-    while (tile < a.lane_tiles) {
-        // ... and every further tile's while the wavefront walks the one before it
-        const size_t next_tile = tile + stride;
-        const size_t next_e = next_tile * 64 + lane;
-        const bool next_live = next_tile < a.lane_tiles && next_e < a.batch;
-        LaneInputs<CMP> next_in = {};
-        if (next_live) next_in = load_lane_inputs<CMP, MODE>(a, p, next_e);
-        if (live) eval_lane_walk<CMP, MODE>(a, p, L, e, in);
-        tile = next_tile; e = next_e; live = next_live; in = next_in;
+    for (size_t tile = slot; tile < a.lane_tiles; tile += stride) {
+        const size_t e = tile * 64 + lane;
+        if (e < a.batch) eval_lane_walk<CMP, MODE>(a, p, L, e, load_lane_inputs<CMP, MODE>(a, p, e));
     }
 
     if (a.quad_tiles != 0) {
