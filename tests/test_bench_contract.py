@@ -39,3 +39,33 @@ def test_json_line_has_the_agreed_fields():
         assert key in c, key
     assert c["kind"] == "oracle" and c["cores"] >= 1 and c["value"] > 0
     assert j["value"] > 100 * c["value"]          # sanity: the GPU path is not the oracle in disguise
+
+
+@pytest.mark.gpu
+def test_default_line_carries_both_rooflines_every_configuration_and_the_clock():
+    """The default command (shortened: fewer steps and repetitions, a smaller oracle sample) on the
+    2^22 configuration: KeyGen roofline beside the Eval one, the sustained clock, the oracle baseline
+    with its parity statement, and one entry per benchmark configuration."""
+    run = subprocess.run([sys.executable, BENCH, "--steps", "2", "--warmup", "1", "--config-reps", "3", "--cpu-sample", "16384"],
+                         capture_output=True, text=True, timeout=900)
+    assert run.returncode == 0, run.stderr
+    lines = [l for l in run.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    j = json.loads(lines[0])
+    assert j["config"]["batch"] == 1 << 22 and "2^22" not in j["metric"] and j["metric"].startswith("FSS comparison evals/sec per party")
+    r = j["roofline"]
+    assert r["bound"] == "lds" and r["kernel"] == "eval_kernel<cmp>" and 0.5 < r["frac"] < 1.1
+    assert r["frac_issued"] < r["frac"] and r["traffic"] is not None
+    assert abs(r["traffic"] / r["traffic_algorithmic"] - 1) < 0.01
+    g = r["gen"]
+    assert g["kernel"] == "gen_kernel<cmp>" and 0.5 < g["frac"] < 1.2 and g["frac_issued"] < g["frac"]
+    assert 1000 < j["sustained_clock_mhz"] < 2600 and j["nominal_clock_mhz"] == 2400
+    assert "parity" in j["cpu_baseline"] and "same alpha" in j["cpu_baseline"]["sample"]
+    names = [c["name"] for c in j["configs"]]
+    assert names == ["config1", "config2", "config3", "config4", "config5", "n16"]
+    for c in j["configs"]:
+        for key in ("eval_ms_median", "eval_ms_min", "gen_ms_median", "evals_per_s_per_party", "gen_key_pairs_per_s", "eval_kernel"):
+            assert key in c, (c["name"], key)
+        for op in ("eval", "gen"):
+            assert 0 < c[op]["lds_frac_issued"] <= c[op]["lds_frac_algorithmic"] * 1.02 and 0 < c[op]["hbm_frac"] < 1 and 0 < c[op]["alu_frac"] < 1
+    assert j["configs"][0]["eval_kernel"] == "eval_quad_kernel<cmp>" and j["configs"][1]["kind"] == "eq" and j["configs"][3]["rounds"] == 8
