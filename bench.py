@@ -81,6 +81,24 @@ def median(v):
     return statistics.median(v)
 
 
+WARM_MS = 40.0
+
+
+def warm_up(step, at_least, min_ms=WARM_MS):
+    """Untimed repetitions of `step` before a measurement: at least `at_least`, and at least `min_ms` of
+    them.  After an idle stretch the chip's power management needs about 30 ms of load to settle:
+    launch times first rise by a fifth and then fall to their steady value (see the per-dispatch
+    traces behind profiles/), so a few short repetitions alone would time that transient."""
+    import torch
+    torch.cuda.synchronize()
+    t0, done = time.perf_counter(), 0
+    while done < at_least or (time.perf_counter() - t0) * 1e3 < min_ms:
+        step()
+        torch.cuda.synchronize()
+        done += 1
+    return done
+
+
 def lds_gbs(kind, op, n, batch, ms):
     return batch * aes_blocks(kind, op, n) * LOOKUPS_PER_BLOCK * 4 / (ms * 1e-3) / 1e9
 
@@ -156,14 +174,31 @@ def split_marks(marks):
     return gen_ms, ev_ms
 
 
+def sig(v, digits=5):
+    """Floats of the JSON line to `digits` significant figures (the line stays short enough to be read from a log tail)."""
+    if isinstance(v, float):
+        return float(f"{v:.{digits}g}")
+    if isinstance(v, dict):
+        return {k: sig(x, digits) for k, x in v.items()}
+    if isinstance(v, (list, tuple)):
+        return [sig(x, digits) for x in v]
+    return v
+
+
 def entry(name, kind, n, batch, gen_ms, ev_ms, what):
+    """One configuration's figures in the short form CONFIGS_LEGEND describes."""
     ek, gk, layout = kernel_names(kind, batch)
     em, gm = median(ev_ms), median(gen_ms)
-    return {"name": name, "workload": what, "kind": kind, "n": n, "batch": batch, "register_layout": layout,
-            "eval_kernel": ek, "gen_kernel": gk, "eval_launches_timed": len(ev_ms), "gen_launches_timed": len(gen_ms),
-            "eval_ms_median": em, "eval_ms_min": min(ev_ms), "gen_ms_median": gm, "gen_ms_min": min(gen_ms),
-            "evals_per_s_per_party": batch / (em * 1e-3), "gen_key_pairs_per_s": batch / (gm * 1e-3),
-            "eval": fractions(name, kind, "eval", n, batch, em), "gen": fractions(name, kind, "gen", n, batch, gm)}
+    fe, fg = fractions(name, kind, "eval", n, batch, em), fractions(name, kind, "gen", n, batch, gm)
+    short = lambda f: [f["lds_frac_algorithmic"], f.get("lds_frac_issued"), f.get("alu_frac"), f["hbm_frac"]]
+    return {"name": name, "kind": kind, "n": n, "batch": batch, "kernel": ek,
+            "eval_ms": [em, min(ev_ms)], "gen_ms": [gm, min(gen_ms)],
+            "evals_per_s": batch / (em * 1e-3), "pairs_per_s": batch / (gm * 1e-3),
+            "eval_frac": short(fe), "gen_frac": short(fg)}
+
+
+CONFIGS_LEGEND = ("kernel: the Eval kernel that ran; *_ms: [median, min] over the timed launches; evals_per_s: per party; pairs_per_s: KeyGen; "
+                  "*_frac: [LDS lookups the algorithm states, LDS lookups issued, vector ALU, HBM] as fractions of the nominal peaks")
 
 
 def config_workload(name):
@@ -189,16 +224,16 @@ def bench_pair(name, dev, reps, warm):
     kind, n, w, what = config_workload(name)
     d = Device(kind, n, w, dev)
     stream = torch.cuda.current_stream()
-    for _ in range(warm):
-        d.step(stream)
-    torch.cuda.synchronize()
+    warmed = warm_up(lambda: d.step(stream), warm)
     marks = []
     for _ in range(reps):
         d.step(stream, marks)
     torch.cuda.synchronize()
     d.check_reconstruction()
     gen_ms, ev_ms = split_marks(marks)
-    return entry(name, kind, n, d.batch, gen_ms, ev_ms, what)
+    out = entry(name, kind, n, d.batch, gen_ms, ev_ms, what)
+    out["warmup_steps"] = warmed
+    return out
 
 
 def bench_rounds(dev, reps, warm):
@@ -222,13 +257,14 @@ def bench_rounds(dev, reps, warm):
         g = W.maxpool_round_keys(W.BASE_SEED + 4, rnd, B)
         kk = [torch.empty(fss.cmp_key_bytes(n, B), dtype=torch.uint8, device=dev) for _ in range(2)]
         args = [T(v) for v in (g.alpha, g.r, g.seed0, g.seed1)]
-        for rep in range(warm + max(reps // 4, 2)):                   # KeyGen of the round's 200,704 key pairs
+        if rnd == 1:
+            warm_up(lambda: fss.cmp_gen(n, B, *args, kk[0], kk[1], stream=stream), warm)
+        for rep in range(max(reps // 4, 2)):                          # KeyGen of the round's 200,704 key pairs
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(stream)
             fss.cmp_gen(n, B, *args, kk[0], kk[1], stream=stream)
             e1.record(stream)
-            if rep >= warm:
-                gen_ms.append((e0, e1))
+            gen_ms.append((e0, e1))
         keys.append(kk)
         d_alpha.append(args[0])
     torch.cuda.synchronize()
@@ -251,9 +287,7 @@ def bench_rounds(dev, reps, warm):
             m = torch.where((o[0] + o[1]) == 1, d_taps[k], m)   # 1{m - w_k <= 0}: the tap is at least the running maximum
         return m
 
-    for _ in range(warm):
-        step(False)
-    torch.cuda.synchronize()
+    warmed = warm_up(lambda: step(False), warm)
     t0 = time.perf_counter()
     for _ in range(reps):
         m = step(True)
@@ -264,8 +298,7 @@ def bench_rounds(dev, reps, warm):
     ev_ms = [a.elapsed_time(b) for a, b in marks]
     out = entry("config4", "cmp", n, B, gen_ms, ev_ms,
                 "running-maximum max-pool 3x3/2 of 64x112x112: 8 dependent rounds x both parties' Eval of 200,704 elements, fresh keys per round")
-    out.update({"rounds": 8, "eval_ms_sum_of_16": median(ev_ms) * 16, "step_ms_with_glue_in_the_clear": wall * 1e3 / reps,
-                "agreement_with_plain_maxpool": agree})
+    out.update({"warmup_steps": warmed, "rounds": 8, "step_ms_with_glue": wall * 1e3 / reps, "agrees_with_maxpool": agree})
     return out
 
 
@@ -335,9 +368,9 @@ def cpu_baseline(d, sample):
     oracle.set_threads(0)
     return {
         "value": sample / per_party, "unit": "evals/s/party", "cores": threads, "kind": "oracle",
-        "sample": f"the first {sample} of the {d.batch} elements the GPU step ran on (same alpha, r, seeds, x): Gen {t1 - t0:.2f} s, "
-                  f"Eval party0 {t2 - t1:.2f} s, party1 {t3 - t2:.2f} s",
-        "parity": f"GPU keys (every plane, both parties) and both parties' shares equal the oracle's on those {sample} elements",
+        "sample": f"first {sample} of the {d.batch} elements the GPU step ran on (same alpha, r, seeds, x): Gen {t1 - t0:.2f} s, "
+                  f"Eval {t2 - t1:.2f} + {t3 - t2:.2f} s",
+        "parity": "GPU keys (every plane, both parties) and both shares equal the oracle's on those elements",
         "gen_pairs_per_s": sample / (t1 - t0),
         "one_thread_evals_per_s": small / (t6 - t5), "one_thread_gen_pairs_per_s": small / (t5 - t4),
     }
@@ -384,9 +417,7 @@ def relu_layer_bench(args, dev):
         for j in (0, 1):
             fss.relu_finish(j, n, B, delta[0], delta[1], eps[0], eps[1], ta[j], tb[j], tc[j], z[j], stream=stream)
 
-    for _ in range(args.warmup):
-        step(False)
-    torch.cuda.synchronize()
+    warm_up(lambda: step(False), args.warmup)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step(True)
@@ -475,9 +506,7 @@ def maxpool_layer_bench(args, dev):
         for j in (0, 1):
             fss.dot_finish(j, n, rows, m, dl[0], dl[1], ep[0], ep[1], ta[j], tb[j], tc[j], out[j], stream=stream)
 
-    for _ in range(args.warmup):
-        step(False)
-    torch.cuda.synchronize()
+    warm_up(lambda: step(False), args.warmup)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step(True)
@@ -609,10 +638,10 @@ def main():
         print(json.dumps(streamed_bench(args, dev)))
         return
     if args.workload == "rounds":
-        print(json.dumps(bench_rounds(dev, args.steps, args.warmup)))
+        print(json.dumps(sig(bench_rounds(dev, args.steps, args.warmup))))
         return
     if args.workload == "config":
-        print(json.dumps(bench_named(args.config, dev, args.steps, args.warmup)))
+        print(json.dumps(sig(bench_named(args.config, dev, args.steps, args.warmup))))
         return
 
     B, n = args.batch, N_BITS
@@ -643,19 +672,14 @@ def main():
     ek, gk, layout = kernel_names(kind, B)
     fe, fg = fractions(name, kind, "eval", n, B, eval_ms), fractions(name, kind, "gen", n, B, gen_mean)
 
-    def roofline(kernel, f, op, ms):
+    def roofline(kernel, f, op):
+        # achieved: the algorithm's lookups (AES blocks x 160 x 4 B per element) over the mean launch duration of the
+        # timed steps (HIP events on the launch stream); peak: 32 lookups x 4 B per clock and CU at 2.4 GHz
         return {
             "bound": "lds", "kernel": kernel, "achieved": f["lds_algorithmic_gbs"], "peak": PEAK_LDS_GBS, "unit": "GB/s",
-            "frac": f["lds_frac_algorithmic"],
-            "what": f"{aes_blocks(kind, op, n)} AES blocks x {LOOKUPS_PER_BLOCK} four-byte table lookups per element, over the mean launch "
-                    f"duration ({ms:.4f} ms, HIP events on the launch stream), against 32 lookups x 4 B per clock and CU at 2.4 GHz",
-            "frac_issued": f.get("lds_frac_issued"),
-            "traffic": MEASURED_HBM_BYTES.get(name, {}).get(op),
-            "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy)",
-            "traffic_algorithmic": B * hbm_bytes(kind, op, n),
-            "alu": {"frac": f.get("alu_frac"), "peak": PEAK_LANE_TOPS, "unit": "T 32-bit lane-ops/s"},
-            "hbm": {"achieved": f["hbm_gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": f["hbm_frac"],
-                    "bytes_per_element": hbm_bytes(kind, op, n)},
+            "frac": f["lds_frac_algorithmic"], "frac_issued": f.get("lds_frac_issued"),
+            "traffic": MEASURED_HBM_BYTES.get(name, {}).get(op), "traffic_algorithmic": B * hbm_bytes(kind, op, n),     # HBM bytes per launch
+            "alu_frac": f.get("alu_frac"), "hbm_frac": f["hbm_frac"], "hbm_gbs": f["hbm_gbs"],
         }
 
     out = {
@@ -673,14 +697,14 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{'large' if B >= fss.quad_layout_below() else 'small'} batch: {kind} Gen of {B} keys + both parties' Eval, n=32, "
                                + ("uniform alpha and x" if cmp else "uniform alpha, x = alpha on a tenth of the elements")
-                               + ", SoA keys resident in HBM", "batch": B, "n": n, "lambda": 128, "register_layout": layout},
+                               + ", SoA keys resident in HBM", "batch": B, "n": n, "lambda": 128},
         "eval_ms": eval_ms, "eval_ms_median": median(ev_ms), "eval_ms_min": min(ev_ms),
         "gen_ms": gen_mean, "gen_ms_median": median(gen_ms), "gen_ms_min": min(gen_ms),
         "gen_key_pairs_per_s": B / (gen_mean * 1e-3),
         "step_evals_per_s_incl_gen": 2 * B / (wall / args.steps),
-        "roofline": roofline(ek, fe, "eval", eval_ms),
+        "roofline": roofline(ek, fe, "eval"),
     }
-    out["roofline"]["gen"] = roofline(gk, fg, "gen", gen_mean)
+    out["roofline"]["gen"] = roofline(gk, fg, "gen")
     out["sustained_clock_mhz"] = sustained_clock_mhz(d, dev)
     out["nominal_clock_mhz"] = 2400
     props = torch.cuda.get_device_properties(dev)
@@ -692,11 +716,12 @@ def main():
     torch.cuda.empty_cache()
     wanted = [] if args.configs == "none" else (list(CONFIG_NAMES) if args.configs == "all" else args.configs.split(","))
     if cmp and B == 1 << 22 and wanted:
+        out["configs_legend"] = CONFIGS_LEGEND
         out["configs"] = []
         for cname in wanted:
             out["configs"].append(bench_named(cname, dev, args.config_reps, 2))
             torch.cuda.empty_cache()
-    print(json.dumps(out))
+    print(json.dumps(sig(out), separators=(",", ":")))
 
 
 if __name__ == "__main__":

@@ -33,7 +33,7 @@ def test_json_line_has_the_agreed_fields():
     r = j["roofline"]
     for key in ("bound", "achieved", "peak", "unit", "frac", "traffic"):
         assert key in r, key
-    assert r["bound"] == "lds" and abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-9 and 0 < r["frac"] < 1
+    assert r["bound"] == "lds" and abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-4 and 0 < r["frac"] < 1
     c = j["cpu_baseline"]
     for key in ("value", "unit", "cores", "kind", "sample"):
         assert key in c, key
@@ -64,8 +64,11 @@ def test_default_line_carries_both_rooflines_every_configuration_and_the_clock()
     names = [c["name"] for c in j["configs"]]
     assert names == ["config1", "config2", "config3", "config4", "config5", "n16"]
     for c in j["configs"]:
-        for key in ("eval_ms_median", "eval_ms_min", "gen_ms_median", "evals_per_s_per_party", "gen_key_pairs_per_s", "eval_kernel"):
+        for key in ("eval_ms", "gen_ms", "evals_per_s", "pairs_per_s", "kernel", "warmup_steps"):
             assert key in c, (c["name"], key)
-        for op in ("eval", "gen"):
-            assert 0 < c[op]["lds_frac_issued"] <= c[op]["lds_frac_algorithmic"] * 1.02 and 0 < c[op]["hbm_frac"] < 1 and 0 < c[op]["alu_frac"] < 1
-    assert j["configs"][0]["eval_kernel"] == "eval_quad_kernel<cmp>" and j["configs"][1]["kind"] == "eq" and j["configs"][3]["rounds"] == 8
+        assert c["eval_ms"][1] <= c["eval_ms"][0] and c["gen_ms"][1] <= c["gen_ms"][0]          # [median, min]
+        for lds, issued, alu, hbm in (c["eval_frac"], c["gen_frac"]):
+            assert 0 < issued <= lds * 1.02 and 0 < hbm < 1 and 0 < alu < 1
+    assert "median" in j["configs_legend"]
+    assert len(lines[0]) < 4000, "the line must stay short enough to survive a log tail"
+    assert j["configs"][0]["kernel"] == "eval_quad_kernel<cmp>" and j["configs"][1]["kind"] == "eq" and j["configs"][3]["rounds"] == 8
