@@ -61,16 +61,16 @@ def hbm_bytes(kind: str, op: str, n: int) -> int:
 # tests/test_profiles_match_bench.py checks every figure against the summaries under profiles/.
 ISSUED = {          # profiles/configs_sq_counters.txt
     "config1": {"eval": {"lds": 2555904, "valu": 7179264}, "gen": {"lds": 7503872, "valu": 18807808}},
-    "config2": {"eval": {"lds": 83918848, "valu": 168050688}, "gen": {"lds": 311459840, "valu": 527695872}},
-    "config3": {"eval": {"lds": 116588544, "valu": 223313920}, "gen": {"lds": 343310336, "valu": 593693696}},
-    "config4": {"eval": {"lds": 29171712, "valu": 56300544}, "gen": {"lds": 85852160, "valu": 149083904}},
-    "config5": {"eval": {"lds": 608206848, "valu": 1151287296}, "gen": {"lds": 1791000576, "valu": 3062915072}},
-    "n16": {"eval": {"lds": 304119808, "valu": 577716224}, "gen": {"lds": 895516672, "valu": 1536188416}},
+    "config2": {"eval": {"lds": 83918848, "valu": 167620608}, "gen": {"lds": 311459840, "valu": 527695872}},
+    "config3": {"eval": {"lds": 116588544, "valu": 221751296}, "gen": {"lds": 343310336, "valu": 593693696}},
+    "config4": {"eval": {"lds": 29171712, "valu": 55873024}, "gen": {"lds": 85852160, "valu": 149083904}},
+    "config5": {"eval": {"lds": 608206848, "valu": 1143119872}, "gen": {"lds": 1791000576, "valu": 3062915072}},
+    "n16": {"eval": {"lds": 304119808, "valu": 572694528}, "gen": {"lds": 895516672, "valu": 1536188416}},
 }
 MEASURED_HBM_BYTES = {   # profiles/hbm_counters.txt
-    "config2": {"eval": 574736399, "gen": 1183091752},
-    "config3": {"eval": 656433435, "gen": 1330166602},
-    "config5": {"eval": 3405842163, "gen": 6946302624},
+    "config2": {"eval": 574723632, "gen": 1183088236},
+    "config3": {"eval": 656444549, "gen": 1330152485},
+    "config5": {"eval": 3405846007, "gen": 6946244338},
 }
 
 CONFIG_NAMES = ("config1", "config2", "config3", "config4", "config5", "n16")     # the `configs` block of the default run
