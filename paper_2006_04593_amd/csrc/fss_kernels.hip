@@ -291,10 +291,11 @@ __device__ __forceinline__ void eval_quad_walk(const EvalArgs &a, const EvalPlan
 
 // Batches from the layout switch on.  Elements [0, 64 lane_tiles) are walked one lane per element:
 // the unit of work is a 64-element tile per wavefront, and tile (p W + w) G + g goes to wavefront w
-// of workgroup g in pass p (G workgroups of W wavefronts).  What is left after the last FULL pass
-// would keep only a few wavefronts per CU busy for a whole walk; when it is short, the host hands it
-// over as quad_tiles tiles of 16 elements, walked four lanes per element by the same wavefronts
-// (four times the wavefronts, a quarter of the dependent chain each).
+// of workgroup g in pass p (G workgroups of W wavefronts), so that every workgroup holds the same
+// number of tiles.  The elements behind them -- a short rest after the last full pass and the last,
+// partial row of tiles, as the host's split_work decides -- come as quad_tiles tiles of 16 elements,
+// walked four lanes per element by the same wavefronts (four times the wavefronts, a quarter of
+// the dependent chain each).
 template <bool CMP, int MODE>
 __global__ __launch_bounds__(kThreads) void eval_kernel(EvalArgs a)
 {
@@ -838,10 +839,11 @@ static LaunchShape shape_for(size_t elems, const DeviceInfo &d, size_t tile_elem
 
 // The quad layout (four lanes per element) serves batches that would leave the CUs short of
 // wavefronts with one lane per element.  Measured on MI355X, for KeyGen and Eval, comparison and
-// equality alike: the quad layout is faster below about 8 wavefronts of 64 elements per CU (2.1x
-// for Eval and 2.2x for KeyGen at 16,384 elements), slower above (by 25-30 % on large batches).
+// equality alike: the quad layout is faster below about 8 wavefronts of 64 elements per CU (2.4x
+// for Eval and 2.3x for KeyGen at 16,384 elements, still 5 % at 114,688), slower above (by 25-30 %
+// on large batches).
 #ifndef FSS_QUAD_BELOW
-#define FSS_QUAD_BELOW 8
+#define FSS_QUAD_BELOW 8        // -D override: how the crossover was measured (builds with other values, same box)
 #endif
 constexpr size_t kQuadBelowWavesPerCu = FSS_QUAD_BELOW;
 
@@ -876,7 +878,7 @@ struct WorkSplit {
 };
 
 #ifndef FSS_QUAD_TAIL_BELOW
-#define FSS_QUAD_TAIL_BELOW 8
+#define FSS_QUAD_TAIL_BELOW 8   // -D override, as for FSS_QUAD_BELOW
 #endif
 constexpr size_t kQuadTailBelowWavesPerCu = FSS_QUAD_TAIL_BELOW;
 
