@@ -289,6 +289,107 @@ __device__ __forceinline__ void eval_quad_walk(const EvalArgs &a, const EvalPlan
     if (col == 0) store_share<MODE>(a, e, acc, mask);
 }
 
+// Comparison Eval with EIGHT lanes per element, for the smallest batches.  With four lanes per
+// element a wavefront issues the lookups, combines and addresses of both blocks of a level (26
+// instructions per AES round), and while it is the only wavefront on its SIMD that issue stream,
+// not the LDS round trip, is what a round costs (measured: 164 clocks per round for two blocks in
+// one wavefront, 124 for one block each in two wavefronts of a SIMD).  Here the two blocks of a
+// level sit on two quads of different halves of a 16-lane row -- lanes 0-3 / 4-7 of a row walk the
+// x[i] child of elements 2r / 2r + 1, lanes 8-11 / 12-15 their sigma/tau block -- so a wavefront
+// covers 8 elements, there are twice as many wavefronts, and each issues half as much per round.
+// One DPP row rotation by 8 per level hands each quad the other one's block; from there both
+// quads carry the same walk, and lane 0 of the child quad writes the result.
+struct OctoKeys {
+    QuadKeys q;      // q.k[0], q.k[1]: PRG keys 1 and 2 (child quad) or PRG key 3 twice (sigma/tau quad); q.k[2] unused
+};
+
+__device__ __forceinline__ OctoKeys load_octo_keys(uint32_t col, uint32_t half)
+{
+    OctoKeys o;
+#pragma unroll
+    for (int r = 0; r < 11; r++) {
+        o.q.k[0][r] = c_aes.rk[half ? 2 : 0][4 * r + col];
+        o.q.k[1][r] = c_aes.rk[half ? 2 : 1][4 * r + col];
+        o.q.k[2][r] = 0;
+    }
+    return o;
+}
+
+// lane i of a 16-lane row reads lane (i + 8) mod 16
+__device__ __forceinline__ uint32_t row_swap_halves(uint32_t v) { return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x128, 0xf, 0xf, true); }
+
+template <int MODE, bool BALANCE>
+__device__ __forceinline__ void eval_octo_walk(const EvalArgs &a, const EvalPlanes &p, const LaneBase L, const OctoKeys &K, size_t e,
+                                               uint32_t col, uint32_t half)
+{
+    const int n = a.n;
+    const uint32_t mask = ring_mask(n);
+    const uint32_t keep = col == 0 ? ~1u : ~0u;
+    const uint32_t hm = 0u - half;                        // all ones in the sigma/tau quad
+    const uint32_t *seed_w = reinterpret_cast<const uint32_t *>(p.seed);
+    const uint32_t *scw_w = reinterpret_cast<const uint32_t *>(p.scw);
+    uint32_t s = seed_w[4 * e + col] & keep;
+    uint32_t t = (uint32_t)a.party;
+    const uint4 c = reinterpret_cast<const uint4 *>(p.ctrl)[e];
+    const uint32_t tcw[2] = { c.x, c.y }, taucw[2] = { c.z, c.w };
+    uint32_t xin = a.x[e];
+    if constexpr (MODE != kPlain) xin += a.x2[e];
+    const uint32_t x = xin & mask;
+    uint32_t acc = 0;
+
+    uint32_t scw_next = scw_w[4 * e + col];
+    uint32_t sig_next = p.sig[e], leaf_next = p.leaf[e];
+    int next_drop = tile_priority_start(n, BALANCE);
+    for (int i = 0; i < n; i++) {
+        if constexpr (BALANCE) {
+            if (i == next_drop) next_drop = lower_priority(i, n);
+        }
+        const uint32_t scw = scw_next, sigcw = sig_next, leaf = leaf_next;
+        if (i + 1 < n) {
+            const size_t pe = (size_t)(i + 1) * p.bp + e;
+            scw_next = scw_w[4 * pe + col];
+            sig_next = p.sig[pe]; leaf_next = p.leaf[pe];
+        }
+        const uint32_t b = (x >> (n - 1 - i)) & 1u;
+        const bool right = b != 0;
+        const uint32_t tm = 0u - t;
+        uint32_t g[1];
+        const uint32_t sin[1] = { s };
+        aes_mmo_quad<0, -1>(g, sin, 0u - b, K.q, L);       // child quad: G_{1+x[i]}(s); sigma/tau quad: G_3(s)
+        const uint32_t other = row_swap_halves(g[0]);
+        const uint32_t child = pick32(hm, other, g[0]);    // both quads now hold both blocks
+        const uint32_t w = pick32(hm, g[0], other);
+        const uint32_t sigL = quad_broadcast<0>(w), sigR = quad_broadcast<1>(w), w2 = quad_broadcast<2>(w);
+        const uint32_t sigma = ((right ? sigR : sigL) ^ (sigcw & tm)) & mask;
+        const uint32_t tau = ((w2 >> b) ^ (t & ((right ? taucw[1] : taucw[0]) >> i))) & 1u;
+        acc += (tau ? leaf : 0u) + sigma;
+        const uint32_t t_child = quad_broadcast<0>(child) & 1u;
+        s = (child & keep) ^ (scw & tm);
+        t = t_child ^ (t & ((right ? tcw[1] : tcw[0]) >> i) & 1u);
+    }
+    acc += (t ? p.last[e] : 0u) + (quad_broadcast<3>(s) & mask);
+    if (col == 0 && half == 0) store_share<MODE>(a, e, acc, mask);
+}
+
+template <int MODE, bool BALANCE>
+__global__ __launch_bounds__(kThreads) void eval_octo_kernel(EvalArgs a)
+{
+    extern __shared__ uint32_t lds[];
+    fill_tables(lds);
+    __syncthreads();
+    const LaneBase L = lane_base(lds);
+    const uint32_t lane = threadIdx.x & 63u, col = lane & 3u, half = (lane >> 3) & 1u;
+    const OctoKeys K = load_octo_keys(col, half);
+    const KeyLayout k = key_layout(true, a.n, a.batch);
+    const EvalPlanes p = eval_planes(a, k);
+    const size_t tiles = (a.batch + 7) / 8;
+    const size_t stride = (size_t)(blockDim.x >> 6) * gridDim.x;
+    for (size_t tile = (size_t)wave_index() * gridDim.x + blockIdx.x; tile < tiles; tile += stride) {
+        const size_t e = tile * 8 + (lane >> 4) * 2 + ((lane >> 2) & 1u);
+        if (e < a.batch) eval_octo_walk<MODE, BALANCE>(a, p, L, K, e, col, half);     // both quads of an element drop out together
+    }
+}
+
 // Batches from the layout switch on.  Elements [0, 64 lane_tiles) are walked one lane per element:
 // the unit of work is a 64-element tile per wavefront, and tile (p W + w) G + g goes to wavefront w
 // of workgroup g in pass p (G workgroups of W wavefronts), so that every workgroup holds the same
@@ -788,6 +889,9 @@ static int prepare_device(DeviceInfo *info)
                               (const void *)eval_quad_kernel<true, kPlain, false>, (const void *)eval_quad_kernel<false, kPlain, false>,
                               (const void *)eval_quad_kernel<true, kSign, false>, (const void *)eval_quad_kernel<true, kReluOpen, false>,
                               (const void *)eval_quad_kernel<false, kSign, false>,
+                              (const void *)eval_octo_kernel<kPlain, true>, (const void *)eval_octo_kernel<kSign, true>,
+                              (const void *)eval_octo_kernel<kReluOpen, true>, (const void *)eval_octo_kernel<kPlain, false>,
+                              (const void *)eval_octo_kernel<kSign, false>, (const void *)eval_octo_kernel<kReluOpen, false>,
                               (const void *)gen_kernel<true>, (const void *)gen_kernel<false>,
                               (const void *)gen_quad_kernel<true, true>, (const void *)gen_quad_kernel<false, true>,
                               (const void *)gen_quad_kernel<true, false>, (const void *)gen_quad_kernel<false, false> };
@@ -851,6 +955,16 @@ static size_t quad_layout_below(const DeviceInfo &d) { return (size_t)d.cus * 64
 
 static bool use_quad_layout(size_t batch, const DeviceInfo &d) { return batch < quad_layout_below(d); }
 
+// The eight-lanes-per-element comparison Eval (see eval_octo_walk) pays while the SIMDs hold one or two
+// wavefronts of the quad layout.  Measured against it, same box: -11 % up to 8,192 elements, -2 %
+// at 12,288, equal at 16,384, -7 % at 20,480, -5 % at 24,576, equal at 32,768, slower beyond.
+#ifndef FSS_OCTO_UPTO
+#define FSS_OCTO_UPTO 8         // in quad wavefronts (16 elements) per CU; -D override, as for FSS_QUAD_BELOW
+#endif
+constexpr size_t kOctoUpToWavesPerCu = FSS_OCTO_UPTO;
+
+static bool use_octo_layout(size_t batch, const DeviceInfo &d) { return batch <= (size_t)d.cus * 16 * kOctoUpToWavesPerCu; }
+
 // Launch through hipLaunchKernel and report ITS return value: the thread's last-error slot (which
 // hipGetLastError would read and clear) may hold an unrelated error of the host application.
 template <typename... P, typename... A>
@@ -909,6 +1023,17 @@ static EvalKernel pick_eval_quad_kernel_b(bool cmp, int mode)
     return mode == kPlain ? eval_quad_kernel<true, kPlain, BALANCE>
          : mode == kSign  ? eval_quad_kernel<true, kSign, BALANCE>
                           : eval_quad_kernel<true, kReluOpen, BALANCE>;
+}
+
+template <bool BALANCE>
+static EvalKernel pick_eval_octo_kernel_b(int mode)
+{
+    return mode == kPlain ? eval_octo_kernel<kPlain, BALANCE> : mode == kSign ? eval_octo_kernel<kSign, BALANCE> : eval_octo_kernel<kReluOpen, BALANCE>;
+}
+
+static EvalKernel pick_eval_octo_kernel(int mode, bool balance)
+{
+    return balance ? pick_eval_octo_kernel_b<true>(mode) : pick_eval_octo_kernel_b<false>(mode);
 }
 
 static EvalKernel pick_eval_quad_kernel(bool cmp, int mode, bool balance)
@@ -972,6 +1097,10 @@ static int eval_common(bool cmp, int mode, int party, int n, size_t batch, const
     a.batch = batch; a.n = n; a.party = party;
     hipStream_t st = static_cast<hipStream_t>(stream);
     a.lane_tiles = 0; a.quad_tiles = 0;
+    if (cmp && use_octo_layout(batch, dev)) {
+        const LaunchShape ls = shape_for(batch, dev, 8);
+        return launch(pick_eval_octo_kernel(mode, ls.balance != 0), ls.grid, ls.threads, kLdsBytes, st, a);
+    }
     if (use_quad_layout(batch, dev)) {
         const LaunchShape ls = shape_for(batch, dev, 16);
         return launch(pick_eval_quad_kernel(cmp, mode, ls.balance != 0), ls.grid, ls.threads, kLdsBytes, st, a);

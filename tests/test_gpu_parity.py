@@ -98,6 +98,18 @@ def test_both_layouts_around_the_switch(kind, n, offset):
     check_full(kind, n, w.gen, x)
 
 
+# The comparison Eval of at most fss.quad_layout_below() / 4 elements runs eight lanes per element
+# (KeyGen and the equality Eval four); both sides of that switch, ragged.
+@pytest.mark.parametrize("n,offset", [(32, -9), (32, -1), (32, 0), (32, 1), (32, 17), (12, -3), (16, 5)])
+def test_around_the_eight_lane_switch(n, offset):
+    batch = fss.quad_layout_below() // 4 + offset
+    w = W.uniform_workload("cmp", n, batch, seed=6000 + 10 * n + offset)
+    x = w.x.copy()
+    x[::5] = w.gen.alpha[::5]
+    x &= np.uint32(W.ring_mask(n))
+    check_full("cmp", n, w.gen, x)
+
+
 # From the switch on, full passes (one 64-element tile for every wavefront of the grid: twice
 # fss.quad_layout_below() elements) run one lane per element, and what is left after the last full
 # pass runs four lanes per element INSIDE THE SAME LAUNCH when it is shorter than the switch, one lane
