@@ -60,7 +60,7 @@ def hbm_bytes(kind: str, op: str, n: int) -> int:
 # 64 lanes each) and HBM traffic per launch (FETCH_SIZE + WRITE_SIZE scaled by a plain copy).
 # tests/test_profiles_match_bench.py checks every figure against the summaries under profiles/.
 ISSUED = {          # profiles/configs_sq_counters.txt
-    "config1": {"eval": {"lds": 2555904, "valu": 7179264}, "gen": {"lds": 7503872, "valu": 18807808}},
+    "config1": {"eval": {"lds": 2654208, "valu": 9156600}, "gen": {"lds": 7503872, "valu": 18807808}},
     "config2": {"eval": {"lds": 83918848, "valu": 167620608}, "gen": {"lds": 311459840, "valu": 527695872}},
     "config3": {"eval": {"lds": 116588544, "valu": 221751296}, "gen": {"lds": 343310336, "valu": 593693696}},
     "config4": {"eval": {"lds": 29171712, "valu": 55873024}, "gen": {"lds": 85852160, "valu": 149083904}},
@@ -68,9 +68,9 @@ ISSUED = {          # profiles/configs_sq_counters.txt
     "n16": {"eval": {"lds": 304119808, "valu": 572694528}, "gen": {"lds": 895516672, "valu": 1536188416}},
 }
 MEASURED_HBM_BYTES = {   # profiles/hbm_counters.txt
-    "config2": {"eval": 574723632, "gen": 1183088236},
-    "config3": {"eval": 656444549, "gen": 1330152485},
-    "config5": {"eval": 3405846007, "gen": 6946244338},
+    "config2": {"eval": 574715039, "gen": 1183098273},
+    "config3": {"eval": 656432850, "gen": 1330168961},
+    "config5": {"eval": 3405832398, "gen": 6946258098},
 }
 
 CONFIG_NAMES = ("config1", "config2", "config3", "config4", "config5", "n16")     # the `configs` block of the default run
@@ -163,9 +163,13 @@ class Device:
 
 def kernel_names(kind, batch):
     import paper_2006_04593_amd as fss
-    quad = batch < fss.quad_layout_below()
-    return (f"{'eval_quad_kernel' if quad else 'eval_kernel'}<{kind}>", f"{'gen_quad_kernel' if quad else 'gen_kernel'}<{kind}>",
-            "four lanes per element" if quad else "one lane per element (a short rest four lanes per element)")
+    switch = fss.quad_layout_below()
+    quad = batch < switch
+    octo = kind == "cmp" and batch <= switch // 4          # Eval only
+    return (f"{'eval_octo_kernel' if octo else 'eval_quad_kernel' if quad else 'eval_kernel'}<{kind}>",
+            f"{'gen_quad_kernel' if quad else 'gen_kernel'}<{kind}>",
+            "eight lanes per element (KeyGen four)" if octo else "four lanes per element" if quad
+            else "one lane per element (a short rest four lanes per element)")
 
 
 def split_marks(marks):

@@ -71,4 +71,4 @@ def test_default_line_carries_both_rooflines_every_configuration_and_the_clock()
             assert 0 < issued <= lds * 1.02 and 0 < hbm < 1 and 0 < alu < 1
     assert "median" in j["configs_legend"]
     assert len(lines[0]) < 4000, "the line must stay short enough to survive a log tail"
-    assert j["configs"][0]["kernel"] == "eval_quad_kernel<cmp>" and j["configs"][1]["kind"] == "eq" and j["configs"][3]["rounds"] == 8
+    assert j["configs"][0]["kernel"] == "eval_octo_kernel<cmp>" and j["configs"][1]["kind"] == "eq" and j["configs"][3]["rounds"] == 8
