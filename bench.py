@@ -165,10 +165,11 @@ def kernel_names(kind, batch):
     import paper_2006_04593_amd as fss
     switch = fss.quad_layout_below()
     quad = batch < switch
-    octo = kind == "cmp" and batch <= switch // 4          # Eval only
+    octo = kind == "cmp" and batch <= switch // 4          # the equality Eval keeps four lanes
+    gen_octo = batch <= switch // 4
     return (f"{'eval_octo_kernel' if octo else 'eval_quad_kernel' if quad else 'eval_kernel'}<{kind}>",
-            f"{'gen_quad_kernel' if quad else 'gen_kernel'}<{kind}>",
-            "eight lanes per element (KeyGen four)" if octo else "four lanes per element" if quad
+            f"{'gen_octo_kernel' if gen_octo else 'gen_quad_kernel' if quad else 'gen_kernel'}<{kind}>",
+            "eight lanes per element" if octo else "four lanes per element" if quad
             else "one lane per element (a short rest four lanes per element)")
 
 

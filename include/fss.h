@@ -251,8 +251,9 @@ int fss_cmp_eval_streamed_static(int party, int n, size_t batch, size_t chunk, c
  * element; from there on, one lane per element in rows of 64 elements per compute unit (16 rows =
  * 2 * fss_quad_layout_below() elements make a full pass), and what is left after the last full pass
  * -- if it is shorter than fss_quad_layout_below() -- as well as the last partial row run four lanes
- * per element inside the same launch.  The comparison Eval of at most fss_quad_layout_below() / 4
- * elements spreads an element over eight lanes (one quad per PRG block of a level).
+ * per element inside the same launch.  Up to fss_quad_layout_below() / 4 elements, KeyGen and the
+ * comparison Eval spread an element over eight lanes (KeyGen one quad per party, Eval one quad per
+ * PRG block of a level).
  * fss_quad_layout_below() returns that size for the current device, or 0 if the device cannot be
  * queried.
  * The kernels change the priority of their own wavefronts (s_setprio) while they run, so that the

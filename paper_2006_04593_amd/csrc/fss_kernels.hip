@@ -802,6 +802,124 @@ __device__ __forceinline__ void gen_quad_walk(const GenArgs &a, const KeyLayout 
     }
 }
 
+// KeyGen with EIGHT lanes per key pair, for the smallest batches: one quad per PARTY.  With four
+// lanes per pair a wavefront carries all six PRG blocks of a level, 78 instructions per AES round
+// which a lone wavefront issues at about 5 clocks apiece; split by party, two wavefronts of a
+// SIMD issue 39 each and interleave.  Lanes 0-3 / 4-7 of a 16-lane row are party 0 of pairs
+// 2r / 2r + 1, lanes 8-11 / 12-15 party 1 (as in eval_octo_walk); a quad expands its own
+// party's seed, one DPP row rotation by 8 per block hands it the other party's three blocks, the
+// correction words (symmetric in the parties) are formed in both quads, and each quad writes its own
+// party's key.
+template <bool CMP, bool BALANCE>
+__device__ __forceinline__ void gen_octo_walk(const GenArgs &a, const KeyLayout &k, const LaneBase L, const QuadKeys &K, size_t e,
+                                              uint32_t col, uint32_t half)
+{
+    const int n = a.n;
+    const uint32_t mask = ring_mask(n);
+    const uint32_t keep = col == 0 ? ~1u : ~0u;
+    const uint32_t hm = 0u - half;                           // all ones in party 1's quad
+    uint8_t *const key = half ? a.key1 : a.key0;
+    const uint32_t alpha = a.alpha[e] & mask;
+    const uint32_t r = a.alpha_r[e] & mask;
+    uint32_t s = reinterpret_cast<const uint32_t *>(half ? a.seed1 : a.seed0)[4 * e + col] & keep;
+    uint32_t t_mine = half, t_other = half ^ 1u;             // t_j^(1) = j
+    uint32_t ctrl[4] = { 0, 0, 0, 0 };
+    reinterpret_cast<uint32_t *>(key + k.seed)[4 * e + col] = s;
+
+    int next_drop = tile_priority_start(n, BALANCE);
+    for (int i = 0; i < n; i++) {
+        if constexpr (BALANCE) {
+            if (i == next_drop) next_drop = lower_priority(i, n);
+        }
+        const uint32_t abit = (alpha >> (n - 1 - i)) & 1u;
+        uint32_t h[3] = { 0, 0, 0 }, o[3] = { 0, 0, 0 };       // G_1, G_2, G_3 of my party's seed / of the other party's, this lane's column
+        if constexpr (CMP) {
+            const uint32_t in[3] = { s, s, s };
+            aes_mmo_quad<3, 0, 1, 2>(h, in, 0u, K, L);
+        } else {
+            uint32_t h2[2];
+            const uint32_t in[2] = { s, s };
+            aes_mmo_quad<2, 0, 1>(h2, in, 0u, K, L);
+            h[0] = h2[0]; h[1] = h2[1];
+        }
+#pragma unroll
+        for (int m = 0; m < (CMP ? 3 : 2); m++) o[m] = row_swap_halves(h[m]);
+        const uint32_t tL_m = quad_broadcast<0>(h[0]) & 1u, tR_m = quad_broadcast<0>(h[1]) & 1u;
+        const uint32_t tL_o = quad_broadcast<0>(o[0]) & 1u, tR_o = quad_broadcast<0>(o[1]) & 1u;
+        const uint32_t hL = h[0] & keep, hR = h[1] & keep, oL = o[0] & keep, oR = o[1] & keep;
+        const uint32_t km = 0u - abit;                       // all ones iff Keep = R
+        const uint32_t scw = pick32(km, hL ^ oL, hR ^ oR);   // the Lose-side strings
+        const uint32_t tcwL = tL_m ^ tL_o ^ abit ^ 1u;
+        const uint32_t tcwR = tR_m ^ tR_o ^ abit;
+        ctrl[0] |= tcwL << i;
+        ctrl[1] |= tcwR << i;
+
+        uint32_t sigcw = 0, leaf = 0;
+        if constexpr (CMP) {
+            const uint32_t sgL_m = quad_broadcast<0>(h[2]) & mask, sgR_m = quad_broadcast<1>(h[2]) & mask, w_m = quad_broadcast<2>(h[2]);
+            const uint32_t sgL_o = quad_broadcast<0>(o[2]) & mask, sgR_o = quad_broadcast<1>(o[2]) & mask, w_o = quad_broadcast<2>(o[2]);
+            const uint32_t tauL_m = w_m & 1u, tauR_m = (w_m >> 1) & 1u, tauL_o = w_o & 1u, tauR_o = (w_o >> 1) & 1u;
+            sigcw = pick32(km, sgR_m ^ sgR_o, sgL_m ^ sgL_o);                // the Keep-side strings
+            const uint32_t taucwL = tauL_m ^ tauL_o ^ abit;
+            const uint32_t taucwR = tauR_m ^ tauR_o ^ abit ^ 1u;
+            ctrl[2] |= taucwL << i;
+            ctrl[3] |= taucwR << i;
+            // state'_{j, Lose} of either party, then sorted into party 0 / party 1
+            const uint32_t taucw_lose = pick32(km, taucwL, taucwR);
+            const uint32_t sg_m = pick32(km, sgL_m, sgR_m) ^ (sigcw & (0u - t_mine));
+            const uint32_t sg_o = pick32(km, sgL_o, sgR_o) ^ (sigcw & (0u - t_other));
+            const uint32_t tau_m = pick32(km, tauL_m, tauR_m) ^ (t_mine & taucw_lose);
+            const uint32_t tau_o = pick32(km, tauL_o, tauR_o) ^ (t_other & taucw_lose);
+            const uint32_t sg0 = pick32(hm, sg_o, sg_m), sg1 = pick32(hm, sg_m, sg_o), tau1 = pick32(hm, tau_m, tau_o);
+            leaf = (abit - sg0 + sg1) & mask;                 // (-1)^{tau_1} (alpha[i] - sigma_0 + sigma_1)
+            leaf = ((leaf ^ (0u - tau1)) + tau1) & mask;
+        }
+        // both parties move to state_{j, Keep}, corrected with the OLD t_j; this quad keeps its own seed and both control bits
+        const uint32_t tcw_keep = pick32(km, tcwR, tcwL);
+        s = pick32(km, hR, hL) ^ (scw & (0u - t_mine));
+        t_mine = pick32(km, tR_m, tL_m) ^ (t_mine & tcw_keep);
+        t_other = pick32(km, tR_o, tL_o) ^ (t_other & tcw_keep);
+        const size_t pe = (size_t)i * k.bp + e;
+        reinterpret_cast<uint32_t *>(key + k.s_cw)[4 * pe + col] = scw;
+        if constexpr (CMP) {
+            // lane 0 of the quad: sigma_CW, lane 1: CW_leaf, of this party's key
+            if (col < 2) reinterpret_cast<uint32_t *>(key + (col ? k.leaf : k.sigma_cw))[pe] = col ? leaf : sigcw;
+        }
+    }
+    const uint32_t c_m = quad_broadcast<3>(s) & mask, c_o = quad_broadcast<3>(row_swap_halves(s)) & mask;
+    const uint32_t c0 = pick32(hm, c_o, c_m), c1 = pick32(hm, c_m, c_o), t1 = pick32(hm, t_mine, t_other);
+    uint32_t last = (1u - c0 + c1) & mask;                    // CW^(n+1) = (-1)^{t_1} (1 - conv(s_0) + conv(s_1))
+    if (t1) last = (0u - last) & mask;
+    // lane 0: [[alpha]]_j, lane 1: CW^(n+1), of this party's key
+    const uint32_t share = half ? ((alpha - r) & mask) : r;
+    if (col < 2) reinterpret_cast<uint32_t *>(key + (col ? k.last : k.alpha_share))[e] = col ? last : share;
+    if constexpr (CMP) {
+        const uint32_t cw = col == 0 ? ctrl[0] : col == 1 ? ctrl[1] : col == 2 ? ctrl[2] : ctrl[3];
+        reinterpret_cast<uint32_t *>(key + k.ctrl)[4 * e + col] = cw;
+    } else if (col < 2) {
+        reinterpret_cast<uint32_t *>(key + k.ctrl)[2 * e + col] = col == 0 ? ctrl[0] : ctrl[1];
+    }
+}
+
+template <bool CMP, bool BALANCE>
+__global__ __launch_bounds__(kThreads) void gen_octo_kernel(GenArgs a)
+{
+    extern __shared__ uint32_t lds[];
+    fill_tables(lds);
+    __syncthreads();
+    const LaneBase L = lane_base(lds);
+    const QuadKeys K = load_quad_keys();
+    const KeyLayout k = key_layout(CMP, a.n, a.batch);
+    const uint32_t lane = threadIdx.x & 63u, col = lane & 3u, half = (lane >> 3) & 1u;
+    const size_t tiles = k.bp / 8;
+    const size_t stride = (size_t)(blockDim.x >> 6) * gridDim.x;
+    for (size_t tile = (size_t)wave_index() * gridDim.x + blockIdx.x; tile < tiles; tile += stride) {
+        const size_t e = tile * 8 + (lane >> 4) * 2 + ((lane >> 2) & 1u);
+        if (e < a.batch) gen_octo_walk<CMP, BALANCE>(a, k, L, K, e, col, half);     // both quads of a pair drop out together
+        else if (col == 0 && half == 0) zero_padding_element<CMP>(a.key0, a.key1, k, e, a.n);
+    }
+}
+
 // Batches from the layout switch on: the same split of the work as eval_kernel.  The 16-element
 // tiles run to the end of the PADDED batch, so that the padding elements are written too.
 template <bool CMP>
@@ -892,6 +1010,8 @@ static int prepare_device(DeviceInfo *info)
                               (const void *)eval_octo_kernel<kPlain, true>, (const void *)eval_octo_kernel<kSign, true>,
                               (const void *)eval_octo_kernel<kReluOpen, true>, (const void *)eval_octo_kernel<kPlain, false>,
                               (const void *)eval_octo_kernel<kSign, false>, (const void *)eval_octo_kernel<kReluOpen, false>,
+                              (const void *)gen_octo_kernel<true, true>, (const void *)gen_octo_kernel<false, true>,
+                              (const void *)gen_octo_kernel<true, false>, (const void *)gen_octo_kernel<false, false>,
                               (const void *)gen_kernel<true>, (const void *)gen_kernel<false>,
                               (const void *)gen_quad_kernel<true, true>, (const void *)gen_quad_kernel<false, true>,
                               (const void *)gen_quad_kernel<true, false>, (const void *)gen_quad_kernel<false, false> };
@@ -964,6 +1084,16 @@ static bool use_quad_layout(size_t batch, const DeviceInfo &d) { return batch < 
 constexpr size_t kOctoUpToWavesPerCu = FSS_OCTO_UPTO;
 
 static bool use_octo_layout(size_t batch, const DeviceInfo &d) { return batch <= (size_t)d.cus * 16 * kOctoUpToWavesPerCu; }
+
+// KeyGen with eight lanes per key pair (gen_octo_walk).  Measured against four lanes per pair, same
+// box, comparison / equality: -37 % / -40 % up to 8,192 pairs, -21 % / -25 % at 16,384 and 24,576,
+// -8 % / -11 % at 32,768, slower from 40,960 on.
+#ifndef FSS_GEN_OCTO_UPTO
+#define FSS_GEN_OCTO_UPTO 8     // in quad wavefronts (16 pairs) per CU; -D override, as for FSS_QUAD_BELOW
+#endif
+constexpr size_t kGenOctoUpToWavesPerCu = FSS_GEN_OCTO_UPTO;
+
+static bool use_gen_octo_layout(size_t batch, const DeviceInfo &d) { return batch <= (size_t)d.cus * 16 * kGenOctoUpToWavesPerCu; }
 
 // Launch through hipLaunchKernel and report ITS return value: the thread's last-error slot (which
 // hipGetLastError would read and clear) may hold an unrelated error of the host application.
@@ -1063,6 +1193,12 @@ static int gen_common(bool cmp, int n, size_t batch, const uint32_t *d_alpha, co
     a.batch = batch; a.n = n;
     hipStream_t st = static_cast<hipStream_t>(stream);
     a.lane_tiles = 0; a.quad_tiles = 0;
+    if (use_gen_octo_layout(batch, dev)) {
+        const LaunchShape ls = shape_for(padded_batch(batch), dev, 8);
+        void (*kernel)(GenArgs) = ls.balance ? (cmp ? gen_octo_kernel<true, true> : gen_octo_kernel<false, true>)
+                                             : (cmp ? gen_octo_kernel<true, false> : gen_octo_kernel<false, false>);
+        return launch(kernel, ls.grid, ls.threads, kLdsBytes, st, a);
+    }
     if (use_quad_layout(batch, dev)) {
         const LaunchShape ls = shape_for(padded_batch(batch), dev, 16);
         void (*kernel)(GenArgs) = ls.balance ? (cmp ? gen_quad_kernel<true, true> : gen_quad_kernel<false, true>)

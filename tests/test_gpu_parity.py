@@ -98,16 +98,17 @@ def test_both_layouts_around_the_switch(kind, n, offset):
     check_full(kind, n, w.gen, x)
 
 
-# The comparison Eval of at most fss.quad_layout_below() / 4 elements runs eight lanes per element
-# (KeyGen and the equality Eval four); both sides of that switch, ragged.
+# Up to fss.quad_layout_below() / 4 elements, KeyGen (comparison and equality) and the comparison Eval
+# run eight lanes per element (the equality Eval four); both sides of that switch, ragged.
+@pytest.mark.parametrize("kind", ["cmp", "eq"])
 @pytest.mark.parametrize("n,offset", [(32, -9), (32, -1), (32, 0), (32, 1), (32, 17), (12, -3), (16, 5)])
-def test_around_the_eight_lane_switch(n, offset):
+def test_around_the_eight_lane_switch(kind, n, offset):
     batch = fss.quad_layout_below() // 4 + offset
-    w = W.uniform_workload("cmp", n, batch, seed=6000 + 10 * n + offset)
+    w = W.uniform_workload(kind, n, batch, seed=6000 + 10 * n + offset)
     x = w.x.copy()
     x[::5] = w.gen.alpha[::5]
     x &= np.uint32(W.ring_mask(n))
-    check_full("cmp", n, w.gen, x)
+    check_full(kind, n, w.gen, x)
 
 
 # From the switch on, full passes (one 64-element tile for every wavefront of the grid: twice
