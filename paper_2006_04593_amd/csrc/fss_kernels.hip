@@ -114,15 +114,13 @@ __device__ __forceinline__ EvalPlanes eval_planes(const EvalArgs &a, const KeyLa
     return p;
 }
 
-// What one lane reads before the first level of its element (one lane per element): requested a whole
-// tile ahead, so that it is in registers when the walk starts.
+// What one lane reads before the first level of its element (one lane per element).
 template <bool CMP>
 struct LaneInputs {
     uint4 seed;
     uint4 ctrl;                 // t_CW^L, t_CW^R, tau_CW^L, tau_CW^R (equality: the first two)
     uint32_t x;
-    uint4 scw;                  // correction words of level 1
-    uint32_t sig, leaf;
+    uint32_t last;              // CW^(n+1), used after the last level
 };
 
 template <bool CMP, int MODE>
@@ -139,9 +137,7 @@ __device__ __forceinline__ LaneInputs<CMP> load_lane_inputs(const EvalArgs &a, c
     uint32_t xin = a.x[e];
     if constexpr (MODE != kPlain) xin += a.x2[e];        // the reveal: x = alpha + y
     in.x = xin;
-    in.scw = p.scw[e];
-    in.sig = 0; in.leaf = 0;
-    if constexpr (CMP) { in.sig = p.sig[e]; in.leaf = p.leaf[e]; }
+    in.last = p.last[e];
     return in;
 }
 
@@ -172,19 +168,16 @@ __device__ __forceinline__ void eval_lane_walk(const EvalArgs &a, const EvalPlan
     const uint32_t x = in.x & mask;
     uint32_t acc = 0;
 
-    // correction words are fetched one level ahead of their use
-    uint4 scw_next = in.scw;
-    uint32_t sig_next = in.sig, leaf_next = in.leaf;
     int next_drop = tile_priority_start(n, true);
     for (int i = 0; i < n; i++) {                   // level i + 1
         if (i == next_drop) next_drop = lower_priority(i, n);
-        const uint4 scw = scw_next;
-        const uint32_t sigcw = sig_next, leaf = leaf_next;
-        if (i + 1 < n) {
-            const size_t pe = (size_t)(i + 1) * p.bp + e;
-            scw_next = p.scw[pe];
-            if constexpr (CMP) { sig_next = p.sig[pe]; leaf_next = p.leaf[pe]; }
-        }
+        // The level's correction words are requested here and used after its AES blocks, which at the
+        // occupancy this layout runs at take several HBM round trips (fetching a level ahead instead
+        // costs twelve register moves a level to rotate "next" into "current").
+        const size_t pe = (size_t)i * p.bp + e;
+        const uint4 scw = p.scw[pe];
+        uint32_t sigcw = 0, leaf = 0;
+        if constexpr (CMP) { sigcw = p.sig[pe]; leaf = p.leaf[pe]; }
         const uint32_t b = (x >> (n - 1 - i)) & 1u;  // x[i], most significant first
         const bool right = b != 0;
         const uint32_t pick = 0u - b;                // all ones iff x[i] = 1
@@ -216,7 +209,7 @@ __device__ __forceinline__ void eval_lane_walk(const EvalArgs &a, const EvalPlan
         s[3] = child[3] ^ (scw.w & tm);
         t = t_child ^ (t & ((right ? tcw[1] : tcw[0]) >> i) & 1u);
     }
-    acc += (t ? p.last[e] : 0u) + (s[3] & mask);     // out_{n+1}
+    acc += (t ? in.last : 0u) + (s[3] & mask);       // out_{n+1}
     store_share<MODE>(a, e, acc, mask);
 }
 
