@@ -61,16 +61,16 @@ def hbm_bytes(kind: str, op: str, n: int) -> int:
 # tests/test_profiles_match_bench.py checks every figure against the summaries under profiles/.
 ISSUED = {          # profiles/configs_sq_counters.txt
     "config1": {"eval": {"lds": 2654208, "valu": 9156600}, "gen": {"lds": 7503872, "valu": 21788672}},
-    "config2": {"eval": {"lds": 83918848, "valu": 167620608}, "gen": {"lds": 311459840, "valu": 527695872}},
-    "config3": {"eval": {"lds": 116588544, "valu": 221751296}, "gen": {"lds": 343310336, "valu": 593693696}},
-    "config4": {"eval": {"lds": 29171712, "valu": 55873024}, "gen": {"lds": 85852160, "valu": 149083904}},
-    "config5": {"eval": {"lds": 608206848, "valu": 1143119872}, "gen": {"lds": 1791000576, "valu": 3062915072}},
-    "n16": {"eval": {"lds": 304119808, "valu": 572694528}, "gen": {"lds": 895516672, "valu": 1536188416}},
+    "config2": {"eval": {"lds": 83918848, "valu": 163463168}, "gen": {"lds": 311459840, "valu": 527695872}},
+    "config3": {"eval": {"lds": 116588544, "valu": 218301440}, "gen": {"lds": 343310336, "valu": 593693696}},
+    "config4": {"eval": {"lds": 29171712, "valu": 55027968}, "gen": {"lds": 85852160, "valu": 149083904}},
+    "config5": {"eval": {"lds": 608206848, "valu": 1124593664}, "gen": {"lds": 1791000576, "valu": 3062915072}},
+    "n16": {"eval": {"lds": 304119808, "valu": 563605504}, "gen": {"lds": 895516672, "valu": 1536188416}},
 }
 MEASURED_HBM_BYTES = {   # profiles/hbm_counters.txt
-    "config2": {"eval": 574731276, "gen": 1183097385},
-    "config3": {"eval": 656442780, "gen": 1330174882},
-    "config5": {"eval": 3405841497, "gen": 6946269534},
+    "config2": {"eval": 574728806, "gen": 1183088332},
+    "config3": {"eval": 656437140, "gen": 1330162535},
+    "config5": {"eval": 3405830699, "gen": 6946240421},
 }
 
 CONFIG_NAMES = ("config1", "config2", "config3", "config4", "config5", "n16")     # the `configs` block of the default run
