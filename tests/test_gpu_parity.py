@@ -290,6 +290,33 @@ def test_binding_rejects_buffers_that_are_too_short_or_not_on_the_gpu():
         fss.argmax_diff_mask(n, 10, 3, torch.zeros(fss.cmp_key_bytes(n, 60), dtype=torch.uint8, device=dev()), i32(30), i32(59))
 
 
+def test_launches_on_two_streams_at_once():
+    """KeyGen on one stream and the two parties' Evals of another batch on a second one, all in flight
+    together (the kernels change their own wavefront priorities while they run): same bytes as one
+    after the other."""
+    n = 32
+    a = W.uniform_workload("cmp", n, fss.quad_layout_below() + 4097, seed=71)
+    b = W.uniform_workload("cmp", n, 50_000, seed=72)
+    ka = gpu_gen("cmp", n, a.gen)
+    want = [gpu_eval("cmp", j, n, ka[j], a.x) for j in (0, 1)]
+    kb_ref = gpu_gen("cmp", n, b.gen)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    xa = to_dev(a.x)
+    outs = [torch.full((a.gen.batch,), -1, dtype=torch.int32, device=dev()) for _ in range(2)]
+    nbytes = fss.cmp_key_bytes(n, b.gen.batch)
+    kb = [torch.zeros(nbytes, dtype=torch.uint8, device=dev()) for _ in range(2)]
+    gargs = [to_dev(v) for v in (b.gen.alpha, b.gen.r, b.gen.seed0, b.gen.seed1)]
+    torch.cuda.synchronize()
+    for rep in range(3):
+        fss.cmp_eval(0, n, a.gen.batch, ka[0], xa, outs[0], stream=s1)
+        fss.cmp_gen(n, b.gen.batch, *gargs, kb[0], kb[1], stream=s2)
+        fss.cmp_eval(1, n, a.gen.batch, ka[1], xa, outs[1], stream=s1)
+    torch.cuda.synchronize()
+    for j in (0, 1):
+        assert np.array_equal(u32(outs[j]), want[j])
+        assert torch.equal(kb[j], kb_ref[j])
+
+
 def test_non_default_stream():
     n, batch = 32, 2048
     w = W.uniform_workload("eq", n, batch, seed=31)
