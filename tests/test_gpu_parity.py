@@ -129,6 +129,20 @@ def test_remainder_after_full_passes(kind, n, passes, rest):
     check_full(kind, n, w.gen, x)
 
 
+def test_seeded_sweep_of_sizes_nobody_picked():
+    """Twenty (kind, n, batch) triples drawn from a fixed seed, batches log-uniform between 1 and
+    four times the lane/quad switch: whatever split into passes, rows, rest tiles and layouts the
+    host computes for them, every key byte and share equals the oracle's."""
+    rng = np.random.default_rng(20060459)
+    top = np.log2(4 * fss.quad_layout_below())
+    for case in range(20):
+        kind = ("cmp", "eq")[int(rng.integers(2))]
+        n = int(rng.choice([1, 5, 8, 12, 16, 17, 24, 28, 31, 32, 32, 32]))
+        batch = int(2 ** rng.uniform(0, top))
+        w = W.uniform_workload(kind, n, batch, seed=9000 + case)
+        check_full(kind, n, w.gen, w.x)
+
+
 def test_the_two_layouts_produce_the_same_bytes():
     """One set of per-element arguments placed in a batch below the switch and, repeated, in a batch
     above it: keys and shares of an element depend on that element's arguments only."""
